@@ -1,0 +1,150 @@
+/*
+ * dllm_hcsa.h -- C ABI of the Head-Centric Sparse Attention library for AMD MI355X (gfx950).
+ *
+ * The library implements the attention hot path of a diffusion-LLM denoising step as
+ * described in dLLM-Serve, Section 4.5 ("Head-Centric Sparse KV Cache Management") and
+ * Section 2.3 ("Two-Phase dLLM Inference Process"):
+ *
+ *   dllm_hcsa_select           per-head importance scores of every cached position against the
+ *                              active block's queries, then a per-head top-k (Section 4.5, Eq. 6
+ *                              and the TopK rule stated under it);
+ *   dllm_hcsa_attend           bidirectional softmax attention of each sequence's queries over each
+ *                              head's own kept rows (Reuse phase, Section 2.3 Eq. 4), with sequences
+ *                              flagged dense attending over all their rows in the same call (the
+ *                              mixed Refresh + Reuse batch of Section 5.3);
+ *   dllm_dense_refresh_attend  dense bidirectional attention, all queries against all keys
+ *                              (Refresh phase, Section 2.3 Eq. 3).
+ *
+ * K and V stay in their dense layout; kept rows are fetched through the index lists at attention time.
+ *
+ * Conventions that hold for every entry point
+ *   Pointers   Members of dllm_batch and the idx / cu_k / seq_mode / o / workspace arguments are
+ *              DEVICE pointers owned by the caller.  The dllm_batch struct itself is read on the host.
+ *   Layout     Packed variable length, token-major, head_dim contiguous:
+ *                q   [total_q , n_q_heads , head_dim]   element strides q_stride_tok , q_stride_head
+ *                k,v [total_kv, n_kv_heads, head_dim]   element strides kv_stride_tok, kv_stride_head
+ *                o   [total_q , n_q_heads , head_dim]   contiguous, same dtype as q
+ *              Sequence b owns query rows cu_q[b]..cu_q[b+1]-1 and KV rows cu_kv[b]..cu_kv[b+1]-1.
+ *              Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *              idx is int32 [n_q_heads, total_k]; head h's kept rows of sequence b are
+ *              idx[h*total_k + cu_k[b] .. h*total_k + cu_k[b+1]-1], positions LOCAL to the sequence.
+ *   Ownership  The library allocates and frees no device memory and keeps no pointer after a call
+ *              returns.  Scratch comes from the caller's workspace, sized by the *_workspace query
+ *              made with the same arguments; workspace must be 256-byte aligned.
+ *   Streams    Work is enqueued on hip_stream (a hipStream_t passed as void*, NULL = default stream).
+ *              Calls return without synchronising; nothing is read back to the host, which is why
+ *              total_* and max_* are host-side scalars.
+ *   Errors     A negative dllm_status is returned and dllm_last_error() describes it.  All argument
+ *              checks are made on the host from scalars and pointer nullness; a failed check launches
+ *              nothing.  Not checked (undefined behaviour if violated): cu_* non-decreasing and
+ *              starting at 0, max_* really bounding the per-sequence values, 0 <= k_b <= L_b, and
+ *              idx entries inside [0, L_b).  NaN inputs are unsupported.
+ */
+#ifndef DLLM_HCSA_H
+#define DLLM_HCSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DLLM_OK = 0,
+  DLLM_ERR_INVALID_ARG = -1,  /* null pointer, bad scalar, inconsistent sizes */
+  DLLM_ERR_UNSUPPORTED = -2,  /* a valid request this build does not implement */
+  DLLM_ERR_WORKSPACE = -3,    /* workspace missing, misaligned or too small */
+  DLLM_ERR_DEVICE = -4        /* the HIP runtime refused a launch */
+} dllm_status;
+
+typedef enum { DLLM_F32 = 0, DLLM_BF16 = 1 } dllm_dtype;
+
+/* Sequence modes for dllm_hcsa_attend. */
+#define DLLM_SEQ_SPARSE 0 /* attend over the rows listed in idx (Reuse) */
+#define DLLM_SEQ_DENSE 1  /* attend over every row of the sequence (Refresh) */
+
+typedef struct {
+  dllm_dtype dtype;            /* element type of q, k, v and o */
+  int32_t batch;               /* number of sequences, >= 1 */
+  int32_t n_q_heads;           /* Hq */
+  int32_t n_kv_heads;          /* Hkv, divides Hq */
+  int32_t head_dim;            /* D: 64 or 128 */
+  const void *q, *k, *v;       /* device */
+  int64_t q_stride_tok, q_stride_head;   /* in elements; head_dim stride is 1 */
+  int64_t kv_stride_tok, kv_stride_head; /* in elements, shared by k and v */
+  const int32_t *cu_q;         /* device, [batch+1] */
+  const int32_t *cu_kv;        /* device, [batch+1] */
+  int32_t total_q, total_kv;   /* cu_q[batch], cu_kv[batch] */
+  int32_t max_q, max_kv;       /* upper bounds on per-sequence query count / KV length */
+  float softmax_scale;         /* multiplies q.k before the softmax; 1/sqrt(D) in the paper */
+} dllm_batch;
+
+/*
+ * Selection (Section 4.5, Eq. 6 with pooling width w, then I^h = TopK(S_h, k)).
+ *
+ * For every sequence b with k_b = cu_k[b+1]-cu_k[b] > 0, every query head h and every position
+ * j < L_b, the score is computed in fp32 in one fixed order so that the kept set is reproducible
+ * bit for bit:
+ *     qsum[d] = sum over the sequence's query rows (its active block), ascending row, fp32 adds
+ *     s[j]    = fma chain over d = 0..D-1 of qsum[d] * K[j, h/G, d], starting from 0
+ *     S[j]    = max of s over positions j - pool_w/2 .. j + pool_w/2 clipped to the sequence
+ * (the sum over the block ranks positions exactly as the block mean does).  The k_b positions kept
+ * are the first k_b under the order "larger S first; equal S: lower position first"; they are
+ * written ascending by position into idx_out (layout above).  Sequences with k_b == 0 are skipped.
+ *
+ * pool_w must be odd and between 1 and 63.  max_k bounds k_b; 1 <= max_k <= max_kv.
+ * max_kv may not exceed 32768 (one sequence's scores are ranked inside one compute unit's LDS).
+ * Returns DLLM_ERR_WORKSPACE if workspace_bytes < dllm_hcsa_select_workspace(batch, max_k).
+ */
+size_t dllm_hcsa_select_workspace(const dllm_batch *batch, int32_t max_k);
+dllm_status dllm_hcsa_select(const dllm_batch *batch,
+                             const int32_t *cu_k, /* device, [batch+1] prefix sums of k_b */
+                             int32_t total_k,     /* cu_k[batch] */
+                             int32_t max_k,
+                             int32_t pool_w,
+                             int32_t *idx_out,    /* device, [n_q_heads, total_k] */
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Attention over kept rows (Section 2.3 Eq. 4 restricted to each head's kept set; Eq. 3 for
+ * sequences flagged dense).  For sequence b, head h, query row i:
+ *     O[i,h,:] = sum_t softmax_t(softmax_scale * Q[i,h,:].K[r_t, h/G, :]) * V[r_t, h/G, :]
+ * where r_t runs over idx[h, cu_k[b] .. cu_k[b+1]) if seq_mode[b] == DLLM_SEQ_SPARSE and over
+ * 0 .. L_b-1 if seq_mode[b] == DLLM_SEQ_DENSE.  No mask, no positional term.  idx need not be
+ * sorted and may repeat a row (it then counts twice).  A sequence with nothing to attend to
+ * (k_b == 0 sparse, or L_b == 0 dense) gets zeros.  Scores, softmax state and accumulators are
+ * fp32; bf16 inputs are multiplied on the matrix cores, fp32 inputs with fp32 arithmetic.
+ *
+ * seq_mode may be NULL (all sparse).  idx and cu_k may be NULL only if total_k == 0.
+ * max_k bounds k_b over sparse sequences (0 allowed when there are none).
+ */
+size_t dllm_hcsa_attend_workspace(const dllm_batch *batch, int32_t max_k);
+dllm_status dllm_hcsa_attend(const dllm_batch *batch,
+                             const int32_t *idx,  /* device, [n_q_heads, total_k] */
+                             const int32_t *cu_k, /* device, [batch+1] */
+                             int32_t total_k, int32_t max_k,
+                             const uint8_t *seq_mode, /* device, [batch] or NULL */
+                             void *o,             /* device, [total_q, n_q_heads, head_dim] */
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Dense bidirectional attention of every sequence's queries over all of its keys
+ * (Section 2.3 Eq. 3): O = Softmax(softmax_scale * Q K^T) V per (sequence, head), no mask.
+ * Same result as dllm_hcsa_attend with every sequence flagged dense.
+ */
+size_t dllm_dense_refresh_attend_workspace(const dllm_batch *batch);
+dllm_status dllm_dense_refresh_attend(const dllm_batch *batch,
+                                      void *o, /* device, [total_q, n_q_heads, head_dim] */
+                                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Text of the calling thread's most recent error ("" if none); static storage, never NULL. */
+const char *dllm_last_error(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t dllm_hcsa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLLM_HCSA_H */

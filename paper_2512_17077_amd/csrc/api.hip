@@ -1,0 +1,228 @@
+// C ABI of libdllm_hcsa: host-side argument checks, workspace plans and kernel dispatch.
+// Every check happens before the first HIP call, so a rejected call launches nothing.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "common.h"
+
+namespace {
+
+thread_local char g_err[320] = "";
+
+dllm_status fail(dllm_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validates the batch descriptor and fills the kernel-side shape.
+dllm_status check_batch(const dllm_batch* b, dllm::Shape* out) {
+  if (b == nullptr) return fail(DLLM_ERR_INVALID_ARG, "batch descriptor is NULL");
+  if (b->dtype != DLLM_F32 && b->dtype != DLLM_BF16)
+    return fail(DLLM_ERR_INVALID_ARG, "dtype %d is neither DLLM_F32 nor DLLM_BF16", int(b->dtype));
+  if (b->batch < 1 || b->batch > 65535) return fail(DLLM_ERR_INVALID_ARG, "batch %d outside 1..65535", b->batch);
+  if (b->n_q_heads < 1 || b->n_kv_heads < 1 || b->n_q_heads > 65535)
+    return fail(DLLM_ERR_INVALID_ARG, "head counts must be positive (Hq=%d, Hkv=%d)", b->n_q_heads, b->n_kv_heads);
+  if (b->n_q_heads % b->n_kv_heads != 0)
+    return fail(DLLM_ERR_INVALID_ARG, "n_q_heads %d is not a multiple of n_kv_heads %d", b->n_q_heads, b->n_kv_heads);
+  if (b->head_dim != 64 && b->head_dim != 128)
+    return fail(DLLM_ERR_INVALID_ARG, "head_dim %d is not 64 or 128", b->head_dim);
+  if (!b->q || !b->k || !b->v) return fail(DLLM_ERR_INVALID_ARG, "q, k and v must be non-NULL");
+  if (!b->cu_q || !b->cu_kv) return fail(DLLM_ERR_INVALID_ARG, "cu_q and cu_kv must be non-NULL");
+  if (b->total_q < 0 || b->total_kv < 0 || b->max_q < 0 || b->max_kv < 0 || b->max_q > b->total_q ||
+      b->max_kv > b->total_kv)
+    return fail(DLLM_ERR_INVALID_ARG, "need 0 <= max_q <= total_q and 0 <= max_kv <= total_kv (got %d/%d, %d/%d)",
+                b->max_q, b->total_q, b->max_kv, b->total_kv);
+  const int es = b->dtype == DLLM_F32 ? 4 : 2;
+  const int64_t per16 = 16 / es;
+  if (b->q_stride_head < b->head_dim || b->kv_stride_head < b->head_dim || b->q_stride_tok < b->head_dim ||
+      b->kv_stride_tok < b->head_dim)
+    return fail(DLLM_ERR_INVALID_ARG, "strides must be at least head_dim elements");
+  if (b->q_stride_tok % per16 || b->q_stride_head % per16 || b->kv_stride_tok % per16 || b->kv_stride_head % per16)
+    return fail(DLLM_ERR_INVALID_ARG, "strides must be multiples of 16 bytes");
+  if (!aligned16(b->q) || !aligned16(b->k) || !aligned16(b->v))
+    return fail(DLLM_ERR_INVALID_ARG, "q, k and v must be 16-byte aligned");
+  if (!std::isfinite(b->softmax_scale)) return fail(DLLM_ERR_INVALID_ARG, "softmax_scale is not finite");
+  out->batch = b->batch;
+  out->hq = b->n_q_heads;
+  out->hkv = b->n_kv_heads;
+  out->group = b->n_q_heads / b->n_kv_heads;
+  out->d = b->head_dim;
+  out->q_tok = b->q_stride_tok;
+  out->q_head = b->q_stride_head;
+  out->kv_tok = b->kv_stride_tok;
+  out->kv_head = b->kv_stride_head;
+  out->total_q = b->total_q;
+  out->total_kv = b->total_kv;
+  out->max_q = b->max_q;
+  out->max_kv = b->max_kv;
+  out->scale = b->softmax_scale;
+  return DLLM_OK;
+}
+
+dllm_status check_workspace(const void* ws, size_t have, size_t need) {
+  if (need == 0) return DLLM_OK;
+  if (ws == nullptr) return fail(DLLM_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(DLLM_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (have < need) return fail(DLLM_ERR_WORKSPACE, "workspace has %zu bytes, %zu are needed", have, need);
+  return DLLM_OK;
+}
+
+dllm_status device_result(hipError_t e, const char* what) {
+  if (e == hipSuccess) return DLLM_OK;
+  return fail(DLLM_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+constexpr int kMaxKvSelect = 32768;
+constexpr int kMaxKvSelectPooled = 16384;
+
+dllm_status check_select_scalars(const dllm_batch* b, int32_t max_k, int32_t pool_w) {
+  if (max_k < 1 || max_k > b->max_kv)
+    return fail(DLLM_ERR_INVALID_ARG, "max_k %d outside 1..max_kv (%d)", max_k, b->max_kv);
+  if (pool_w < 1 || pool_w > 63 || pool_w % 2 == 0)
+    return fail(DLLM_ERR_INVALID_ARG, "pool_w %d must be odd and within 1..63", pool_w);
+  if (b->max_kv > (pool_w == 1 ? kMaxKvSelect : kMaxKvSelectPooled))
+    return fail(DLLM_ERR_UNSUPPORTED, "max_kv %d exceeds the %d positions ranked per sequence (pool_w=%d)", b->max_kv,
+                pool_w == 1 ? kMaxKvSelect : kMaxKvSelectPooled, pool_w);
+  return DLLM_OK;
+}
+
+}  // namespace
+
+namespace dllm {
+
+AttendPlan plan_attend(const Shape& s, dllm_dtype dt, int32_t max_k) {
+  AttendPlan p{};
+  p.chunk_rows = max_k > 0 ? max_k : 1;
+  p.n_chunks = 1;
+  if (dt == DLLM_BF16 && max_k > 0) {
+    // aim at about four workgroups per compute unit; chunks are multiples of the 128 rows four waves take
+    const int64_t units = int64_t(s.batch) * s.hq;
+    int64_t want = 1024 / units;
+    if (want < 1) want = 1;
+    const int64_t most = (max_k + 127) / 128;
+    if (want > most) want = most;
+    int64_t rows = (max_k + want - 1) / want;
+    rows = (rows + 127) / 128 * 128;
+    p.chunk_rows = int32_t(rows);
+    p.n_chunks = int32_t((max_k + rows - 1) / rows);
+  }
+  if (p.n_chunks > 1) {
+    const size_t slots = size_t(p.n_chunks) * size_t(s.total_q) * size_t(s.hq);
+    p.off_po = 0;
+    p.off_pm = align256(slots * s.d * sizeof(float));
+    p.off_pl = p.off_pm + align256(slots * sizeof(float));
+    p.bytes = p.off_pl + align256(slots * sizeof(float));
+  }
+  return p;
+}
+
+}  // namespace dllm
+
+extern "C" {
+
+const char* dllm_last_error(void) { return g_err; }
+
+int32_t dllm_hcsa_version(void) { return 100; }
+
+size_t dllm_hcsa_select_workspace(const dllm_batch* batch, int32_t max_k) {
+  dllm::Shape s;
+  if (check_batch(batch, &s) != DLLM_OK) return 0;
+  (void)max_k;
+  return dllm::plan_select(s).bytes;
+}
+
+dllm_status dllm_hcsa_select(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
+                             int32_t pool_w, int32_t* idx_out, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  dllm::Shape s;
+  dllm_status st = check_batch(batch, &s);
+  if (st != DLLM_OK) return st;
+  if ((st = check_select_scalars(batch, max_k, pool_w)) != DLLM_OK) return st;
+  if (cu_k == nullptr || idx_out == nullptr) return fail(DLLM_ERR_INVALID_ARG, "cu_k and idx_out must be non-NULL");
+  if (total_k < 1 || max_k > total_k)
+    return fail(DLLM_ERR_INVALID_ARG, "need 1 <= max_k <= total_k (got max_k=%d, total_k=%d)", max_k, total_k);
+  if ((st = check_workspace(workspace, workspace_bytes, dllm::plan_select(s).bytes)) != DLLM_OK) return st;
+  g_err[0] = 0;
+  return device_result(dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k,
+                                           total_k, max_k, pool_w, idx_out, workspace,
+                                           static_cast<hipStream_t>(hip_stream)),
+                       "dllm_hcsa_select");
+}
+
+size_t dllm_hcsa_attend_workspace(const dllm_batch* batch, int32_t max_k) {
+  dllm::Shape s;
+  if (check_batch(batch, &s) != DLLM_OK || max_k < 0) return 0;
+  return dllm::plan_attend(s, batch->dtype, max_k).bytes;
+}
+
+dllm_status dllm_hcsa_attend(const dllm_batch* batch, const int32_t* idx, const int32_t* cu_k, int32_t total_k,
+                             int32_t max_k, const uint8_t* seq_mode, void* o, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  dllm::Shape s;
+  dllm_status st = check_batch(batch, &s);
+  if (st != DLLM_OK) return st;
+  if (o == nullptr) return fail(DLLM_ERR_INVALID_ARG, "o must be non-NULL");
+  if (!aligned16(o)) return fail(DLLM_ERR_INVALID_ARG, "o must be 16-byte aligned");
+  if (total_k < 0 || max_k < 0 || max_k > total_k || max_k > batch->max_kv)
+    return fail(DLLM_ERR_INVALID_ARG, "need 0 <= max_k <= min(total_k, max_kv) (got max_k=%d, total_k=%d, max_kv=%d)",
+                max_k, total_k, batch->max_kv);
+  if (cu_k == nullptr && (total_k > 0 || seq_mode == nullptr))
+    return fail(DLLM_ERR_INVALID_ARG, "cu_k may be NULL only when every sequence is flagged dense");
+  if (idx == nullptr && total_k > 0) return fail(DLLM_ERR_INVALID_ARG, "idx is NULL but total_k is %d", total_k);
+  const dllm::AttendPlan plan = dllm::plan_attend(s, batch->dtype, max_k);
+  if ((st = check_workspace(workspace, workspace_bytes, plan.bytes)) != DLLM_OK) return st;
+  g_err[0] = 0;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipSuccess;
+  if (batch->dtype == DLLM_F32) {
+    if (cu_k != nullptr)
+      e = dllm::launch_attend_f32(s, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, idx, cu_k, total_k,
+                                  seq_mode, 0, o, stream);
+    if (e == hipSuccess && seq_mode != nullptr)
+      e = dllm::launch_attend_f32(s, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, idx, cu_k, total_k,
+                                  seq_mode, 1, o, stream);
+  } else {
+    // dense sequences first: they are the long-running part of a mixed batch
+    if (seq_mode != nullptr)
+      e = dllm::launch_attend_dense_bf16(s, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, seq_mode, 1, o,
+                                         stream);
+    if (e == hipSuccess && cu_k != nullptr)
+      e = dllm::launch_attend_sparse_bf16(s, plan, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, idx, cu_k,
+                                          total_k, seq_mode, o, workspace, stream);
+  }
+  return device_result(e, "dllm_hcsa_attend");
+}
+
+size_t dllm_dense_refresh_attend_workspace(const dllm_batch* batch) {
+  (void)batch;
+  return 0;
+}
+
+dllm_status dllm_dense_refresh_attend(const dllm_batch* batch, void* o, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  dllm::Shape s;
+  dllm_status st = check_batch(batch, &s);
+  if (st != DLLM_OK) return st;
+  if (o == nullptr) return fail(DLLM_ERR_INVALID_ARG, "o must be non-NULL");
+  if (!aligned16(o)) return fail(DLLM_ERR_INVALID_ARG, "o must be 16-byte aligned");
+  g_err[0] = 0;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (batch->dtype == DLLM_F32)
+    e = dllm::launch_attend_f32(s, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, nullptr, nullptr, 0,
+                                nullptr, 2, o, stream);
+  else
+    e = dllm::launch_attend_dense_bf16(s, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, nullptr, 2, o,
+                                       stream);
+  return device_result(e, "dllm_dense_refresh_attend");
+}
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Internal declarations shared by the HIP translation units of libdllm_hcsa (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dllm_hcsa.h"
+
+namespace dllm {
+
+constexpr int kWave = 64;
+
+// Element strides and sizes every kernel needs; built once per call on the host.
+struct Shape {
+  int32_t batch, hq, hkv, group, d;
+  int64_t q_tok, q_head, kv_tok, kv_head;  // element strides
+  int32_t total_q, total_kv, max_q, max_kv;
+  float scale;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// ---- selection (select_kernels.hip)
+struct SelectPlan {
+  size_t off_scores, off_qsum, bytes;
+};
+SelectPlan plan_select(const Shape& s);
+hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,
+                         const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t max_k,
+                         int32_t pool_w, int32_t* idx_out, void* ws, hipStream_t st);
+
+// ---- attention over kept rows / all rows (attend_*.hip)
+struct AttendPlan {
+  int32_t chunk_rows;  // kept rows one workgroup walks
+  int32_t n_chunks;    // upper bound on chunks per (sequence, head)
+  size_t off_po, off_pm, off_pl, bytes;
+};
+AttendPlan plan_attend(const Shape& s, dllm_dtype dt, int32_t max_k);
+
+// `which` selects the sequences a launch works on: 0 = those not flagged dense (all, if seq_mode
+// is NULL), attended over their kept rows; 1 = those flagged dense; 2 = every sequence, as dense.
+hipError_t launch_attend_f32(const Shape& s, const void* q, const void* k, const void* v, const int32_t* cu_q,
+                             const int32_t* cu_kv, const int32_t* idx, const int32_t* cu_k, int32_t total_k,
+                             const uint8_t* seq_mode, int which, void* o, hipStream_t st);
+hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const void* q, const void* k,
+                                     const void* v, const int32_t* cu_q, const int32_t* cu_kv, const int32_t* idx,
+                                     const int32_t* cu_k, int32_t total_k, const uint8_t* seq_mode, void* o,
+                                     void* ws, hipStream_t st);
+hipError_t launch_attend_dense_bf16(const Shape& s, const void* q, const void* k, const void* v,
+                                    const int32_t* cu_q, const int32_t* cu_kv, const uint8_t* seq_mode, int which,
+                                    void* o, hipStream_t st);
+
+// ---- device helpers
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (inputs are finite here)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+}  // namespace dllm

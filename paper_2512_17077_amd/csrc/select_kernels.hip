@@ -1,0 +1,294 @@
+// Selection: per-head importance scores (Section 4.5, Eq. 6) and per-head top-k.
+//
+// Three kernels on the caller's stream:
+//   block_qsum_kernel   qsum[b,h,:] = sum of the sequence's block queries (fp32, ascending rows)
+//   score_kernel        one pass over K: s[h,j] = fma chain over d of qsum[h,d] * K[j, h/G, d]
+//   topk_kernel         per (sequence, head): pooled keys in LDS, radix select of the k-th largest,
+//                       ordered compaction (ties to the lower position, output ascending)
+//
+// The score arithmetic is fixed (one fused multiply-add per d, ascending d, one lane owns one key),
+// because the kept set must be reproducible bit for bit.  To keep the HBM reads coalesced while one
+// lane owns a whole row, each wave stages 64 rows through LDS: 16-byte chunks are loaded so that a
+// row's chunks sit in neighbouring lanes, written to LDS with an XOR swizzle, and read back one row
+// per lane without bank conflicts.
+#include "common.h"
+
+namespace dllm {
+
+// ------------------------------------------------------------------ block query sum
+template <typename T>
+__device__ __forceinline__ float widen(const T* p);
+template <>
+__device__ __forceinline__ float widen<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float widen<uint16_t>(const uint16_t* p) { return __uint_as_float(uint32_t(*p) << 16); }
+
+template <typename T>
+__global__ void block_qsum_kernel(const T* __restrict__ q, const int32_t* __restrict__ cu_q,
+                                  const int32_t* __restrict__ cu_k, float* __restrict__ qsum, Shape s) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  if (cu_k[b + 1] == cu_k[b]) return;
+  const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
+  const T* p = q + int64_t(q0) * s.q_tok + int64_t(h) * s.q_head + d;
+  float a = 0.0f;
+  for (int i = 0; i < nq; ++i) a = a + widen<T>(p + int64_t(i) * s.q_tok);
+  qsum[(int64_t(b) * s.hq + h) * s.d + d] = a;
+}
+
+// ------------------------------------------------------------------ score
+constexpr int kScoreWaves = 4;
+constexpr int kScoreRowsPerBlock = kScoreWaves * 64;
+
+template <int CH>
+__device__ __forceinline__ int swz(int row) {
+  // chunk permutation that spreads 16 consecutive rows over the 16 sixteen-byte bank groups
+  constexpr int rows_per_line = CH >= 16 ? 1 : 16 / CH;
+  return (row / rows_per_line) & (CH - 1);
+}
+
+// ES: element bytes (2 = bf16, 4 = fp32); D: head_dim; GT: query heads scored per pass over the tile
+template <int ES, int D, int GT>
+__global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
+    const char* __restrict__ k, const float* __restrict__ qsum, const int32_t* __restrict__ cu_kv,
+    const int32_t* __restrict__ cu_k, float* __restrict__ scores, Shape s) {
+  constexpr int ROWB = D * ES;
+  constexpr int CH = ROWB / 16;   // 16-byte chunks per row
+  constexpr int EPC = 16 / ES;    // elements per chunk
+  __shared__ uint4 tile[kScoreWaves][64 * CH];
+
+  const int b = blockIdx.z, g = blockIdx.y;
+  if (cu_k[b + 1] == cu_k[b]) return;
+  const int kv0 = cu_kv[b], L = cu_kv[b + 1] - kv0;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r0 = blockIdx.x * kScoreRowsPerBlock + wave * 64;
+  if (r0 >= L) return;
+  const int nrows = min(64, L - r0);
+  const char* base = k + (int64_t(kv0 + r0) * s.kv_tok + int64_t(g) * s.kv_head) * ES;
+  const int64_t row_pitch = s.kv_tok * ES;
+
+  uint4 regs[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int f = i * 64 + lane, row = f / CH, c = f % CH;
+    regs[i] = make_uint4(0, 0, 0, 0);
+    if (row < nrows) regs[i] = *reinterpret_cast<const uint4*>(base + row * row_pitch + c * 16);
+  }
+  uint4* mine = tile[wave];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int f = i * 64 + lane, row = f / CH, c = f % CH;
+    mine[row * CH + (c ^ swz<CH>(row))] = regs[i];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  const int sw = swz<CH>(lane);
+  for (int hh = 0; hh < s.group; hh += GT) {
+    const int h0 = g * s.group + hh;
+    const float* __restrict__ qs = qsum + (int64_t(b) * s.hq + h0) * D;
+    float acc[GT];
+#pragma unroll
+    for (int t = 0; t < GT; ++t) acc[t] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const uint4 x = mine[lane * CH + (c ^ sw)];
+      float kv[EPC];
+      if constexpr (ES == 2) {
+        kv[0] = bf16_lo(x.x); kv[1] = bf16_hi(x.x); kv[2] = bf16_lo(x.y); kv[3] = bf16_hi(x.y);
+        kv[4] = bf16_lo(x.z); kv[5] = bf16_hi(x.z); kv[6] = bf16_lo(x.w); kv[7] = bf16_hi(x.w);
+      } else {
+        kv[0] = __uint_as_float(x.x); kv[1] = __uint_as_float(x.y);
+        kv[2] = __uint_as_float(x.z); kv[3] = __uint_as_float(x.w);
+      }
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+#pragma unroll
+        for (int t = 0; t < GT; ++t) acc[t] = __builtin_fmaf(qs[t * D + c * EPC + e], kv[e], acc[t]);
+      }
+    }
+    if (lane < nrows) {
+#pragma unroll
+      for (int t = 0; t < GT; ++t)
+        scores[int64_t(h0 + t) * s.total_kv + kv0 + r0 + lane] = acc[t] + 0.0f;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ top-k
+constexpr int kTopkThreads = 512;
+
+__device__ __forceinline__ uint32_t order_key(float f) {
+  // monotone map fp32 -> uint32 (larger float, larger key); +0 and -0 were already merged
+  const uint32_t u = __float_as_uint(f);
+  return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k,
+    int32_t total_kv, int32_t total_k, int32_t pool_w, int32_t lpad, int32_t* __restrict__ idx_out) {
+  extern __shared__ uint32_t dyn[];
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t wave_tot[kTopkThreads / 64];
+  __shared__ uint32_t sh_prefix, sh_k;
+
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int o0 = cu_k[b], kb = cu_k[b + 1] - o0;
+  if (kb == 0) return;
+  const int kv0 = cu_kv[b], L = cu_kv[b + 1] - kv0;
+  const float* __restrict__ src = scores + int64_t(h) * total_kv + kv0;
+  uint32_t* keys = dyn;
+
+  if (pool_w == 1) {
+    for (int j = tid; j < L; j += kTopkThreads) keys[j] = order_key(src[j]);
+  } else {
+    float* raw = reinterpret_cast<float*>(dyn + lpad);
+    for (int j = tid; j < L; j += kTopkThreads) raw[j] = src[j];
+    __syncthreads();
+    const int half = pool_w >> 1;
+    for (int j = tid; j < L; j += kTopkThreads) {
+      const int lo = max(0, j - half), hi = min(L - 1, j + half);
+      float m = raw[lo];
+      for (int t = lo + 1; t <= hi; ++t) m = fmaxf(m, raw[t]);
+      keys[j] = order_key(m);
+    }
+  }
+  __syncthreads();
+
+  // radix select, most significant byte first: the kk-th largest among keys matching `prefix`
+  uint32_t prefix = 0;
+  uint32_t kk = uint32_t(kb);
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int j = tid; j < L; j += kTopkThreads) {
+      const uint32_t key = keys[j];
+      const bool in = pass == 0 || (key >> (shift + 8)) == prefix;
+      if (in) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {
+      uint32_t c[4], t = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { c[i] = hist[255 - (4 * tid + i)]; t += c[i]; }
+      uint32_t incl = t;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if (tid >= off) incl += up;
+      }
+      uint32_t run = incl - t;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (run < kk && kk <= run + c[i]) {
+          sh_prefix = (prefix << 8) | uint32_t(255 - (4 * tid + i));
+          sh_k = kk - run;
+        }
+        run += c[i];
+      }
+    }
+    __syncthreads();
+    prefix = sh_prefix;
+    kk = sh_k;
+  }
+  const uint32_t thr = prefix;   // key of the k-th largest
+  const uint32_t need_eq = kk;   // how many keys equal to it are kept (lowest positions first)
+
+  // ordered compaction: thread t owns positions [t*C, (t+1)*C); C odd keeps LDS reads conflict-free
+  int C = (L + kTopkThreads - 1) / kTopkThreads;
+  C |= 1;
+  const int j0 = min(L, tid * C), j1 = min(L, j0 + C);
+  uint32_t gt = 0, eq = 0;
+  for (int j = j0; j < j1; ++j) {
+    const uint32_t key = keys[j];
+    gt += key > thr;
+    eq += key == thr;
+  }
+  uint32_t packed = gt | (eq << 16);   // both < 2^15
+  uint32_t incl = packed;
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t before = incl - packed;
+  for (int w = 0; w < wave; ++w) before += wave_tot[w];
+  uint32_t gt_before = before & 0xffffu, eq_before = before >> 16;
+  int32_t* __restrict__ out = idx_out + int64_t(h) * total_k + o0;
+  for (int j = j0; j < j1; ++j) {
+    const uint32_t key = keys[j];
+    if (key > thr) {
+      out[gt_before + min(eq_before, need_eq)] = j;
+      ++gt_before;
+    } else if (key == thr) {
+      if (eq_before < need_eq) out[gt_before + eq_before] = j;
+      ++eq_before;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ host side
+SelectPlan plan_select(const Shape& s) {
+  SelectPlan p;
+  p.off_scores = 0;
+  p.off_qsum = align256(size_t(s.hq) * size_t(s.total_kv) * sizeof(float));
+  p.bytes = p.off_qsum + align256(size_t(s.batch) * s.hq * s.d * sizeof(float));
+  return p;
+}
+
+template <int ES, int D>
+static hipError_t launch_score(const Shape& s, const void* k, const float* qsum, const int32_t* cu_kv,
+                               const int32_t* cu_k, float* scores, hipStream_t st) {
+  dim3 grid((s.max_kv + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, s.hkv, s.batch);
+  dim3 block(kScoreWaves * 64);
+  const char* kp = static_cast<const char*>(k);
+  if (s.group % 4 == 0)
+    score_kernel<ES, D, 4><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, s);
+  else if (s.group % 2 == 0)
+    score_kernel<ES, D, 2><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, s);
+  else
+    score_kernel<ES, D, 1><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,
+                         const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t max_k,
+                         int32_t pool_w, int32_t* idx_out, void* ws, hipStream_t st) {
+  (void)max_k;
+  const SelectPlan p = plan_select(s);
+  float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_scores);
+  float* qsum = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_qsum);
+  hipError_t e;
+
+  dim3 qgrid(s.hq, s.batch);
+  if (dt == DLLM_BF16)
+    block_qsum_kernel<uint16_t><<<qgrid, s.d, 0, st>>>(static_cast<const uint16_t*>(q), cu_q, cu_k, qsum, s);
+  else
+    block_qsum_kernel<float><<<qgrid, s.d, 0, st>>>(static_cast<const float*>(q), cu_q, cu_k, qsum, s);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+
+  if (dt == DLLM_BF16)
+    e = s.d == 128 ? launch_score<2, 128>(s, k, qsum, cu_kv, cu_k, scores, st)
+                   : launch_score<2, 64>(s, k, qsum, cu_kv, cu_k, scores, st);
+  else
+    e = s.d == 128 ? launch_score<4, 128>(s, k, qsum, cu_kv, cu_k, scores, st)
+                   : launch_score<4, 64>(s, k, qsum, cu_kv, cu_k, scores, st);
+  if (e != hipSuccess) return e;
+
+  const int32_t lpad = (s.max_kv + 63) & ~63;
+  const size_t lds = size_t(lpad) * 4 * (pool_w == 1 ? 1 : 2);
+  if (lds > 64 * 1024) {   // beyond the default dynamic-LDS limit: raise it for this kernel on this device
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+    if (e != hipSuccess) return e;
+  }
+  topk_kernel<<<dim3(s.hq, s.batch), kTopkThreads, lds, st>>>(scores, cu_kv, cu_k, s.total_kv, total_k, pool_w,
+                                                             lpad, idx_out);
+  return hipGetLastError();
+}
+
+}  // namespace dllm

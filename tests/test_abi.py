@@ -1,0 +1,123 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad
+arguments on the host before touching the GPU (so these run without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_17077_amd import hcsa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "dllm_hcsa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dllm_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = hcsa.lib()
+    names = header_symbols()
+    assert set(names) == set(hcsa.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+    assert L.dllm_hcsa_version() >= 100
+    assert hcsa.last_error() == "" or isinstance(hcsa.last_error(), str)
+
+
+def good_batch():
+    b = hcsa.DllmBatch()
+    b.dtype = hcsa.DLLM_BF16
+    b.batch, b.n_q_heads, b.n_kv_heads, b.head_dim = 2, 8, 2, 128
+    b.q = b.k = b.v = 0x10000            # never dereferenced: these calls fail before any launch
+    b.q_stride_tok, b.q_stride_head = 8 * 128, 128
+    b.kv_stride_tok, b.kv_stride_head = 2 * 128, 128
+    b.cu_q = b.cu_kv = 0x20000
+    b.total_q, b.total_kv, b.max_q, b.max_kv = 64, 500, 32, 300
+    b.softmax_scale = 0.088
+    return b
+
+
+FAKE = ctypes.c_void_p(0x30000)
+
+
+def select_status(b, cu_k=FAKE, total_k=100, max_k=50, pool_w=1, idx=FAKE, ws=FAKE, ws_bytes=1 << 40):
+    return hcsa.lib().dllm_hcsa_select(ctypes.byref(b), cu_k, total_k, max_k, pool_w, idx, ws, ws_bytes, None)
+
+
+def attend_status(b, idx=FAKE, cu_k=FAKE, total_k=100, max_k=50, mode=None, o=FAKE, ws=FAKE, ws_bytes=1 << 40):
+    return hcsa.lib().dllm_hcsa_attend(ctypes.byref(b), idx, cu_k, total_k, max_k, mode, o, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("field,value", [
+    ("dtype", 7), ("batch", 0), ("n_q_heads", 0), ("n_kv_heads", 3), ("head_dim", 96), ("q", 0), ("k", None),
+    ("cu_kv", 0), ("max_kv", 501), ("max_q", -1), ("q_stride_head", 64), ("kv_stride_tok", 257), ("v", 0x10008),
+    ("softmax_scale", float("inf")),
+])
+def test_bad_batch_descriptor_is_rejected_everywhere(field, value):
+    b = good_batch()
+    setattr(b, field, value)
+    assert select_status(b) == hcsa.DLLM_ERR_INVALID_ARG
+    assert hcsa.last_error() != ""
+    assert attend_status(b) == hcsa.DLLM_ERR_INVALID_ARG
+    assert hcsa.lib().dllm_dense_refresh_attend(ctypes.byref(b), FAKE, None, 0, None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert hcsa.lib().dllm_hcsa_select_workspace(ctypes.byref(b), 50) == 0
+
+
+def test_select_scalar_and_workspace_checks():
+    b = good_batch()
+    assert select_status(b, max_k=0) == hcsa.DLLM_ERR_INVALID_ARG
+    assert select_status(b, max_k=301) == hcsa.DLLM_ERR_INVALID_ARG          # > max_kv
+    assert select_status(b, pool_w=2) == hcsa.DLLM_ERR_INVALID_ARG
+    assert select_status(b, pool_w=65) == hcsa.DLLM_ERR_INVALID_ARG
+    assert select_status(b, cu_k=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert select_status(b, idx=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert select_status(b, total_k=10, max_k=50) == hcsa.DLLM_ERR_INVALID_ARG
+    need = hcsa.lib().dllm_hcsa_select_workspace(ctypes.byref(b), 50)
+    assert need >= 8 * 500 * 4 + 2 * 8 * 128 * 4
+    assert select_status(b, ws=None) == hcsa.DLLM_ERR_WORKSPACE
+    assert select_status(b, ws_bytes=need - 1) == hcsa.DLLM_ERR_WORKSPACE
+    assert "workspace" in hcsa.last_error()
+    assert select_status(b, ws=ctypes.c_void_p(0x30010)) == hcsa.DLLM_ERR_WORKSPACE   # misaligned
+    big = good_batch()
+    big.total_kv, big.max_kv = 100000, 40000
+    assert select_status(big) == hcsa.DLLM_ERR_UNSUPPORTED
+    big.max_kv = 20000
+    assert select_status(big, pool_w=3) == hcsa.DLLM_ERR_UNSUPPORTED
+
+
+def test_attend_scalar_checks():
+    b = good_batch()
+    assert attend_status(b, o=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert attend_status(b, max_k=-1) == hcsa.DLLM_ERR_INVALID_ARG
+    assert attend_status(b, max_k=301, total_k=400) == hcsa.DLLM_ERR_INVALID_ARG
+    assert attend_status(b, idx=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert attend_status(b, cu_k=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert attend_status(b, o=ctypes.c_void_p(0x30004)) == hcsa.DLLM_ERR_INVALID_ARG
+    assert hcsa.lib().dllm_dense_refresh_attend(ctypes.byref(b), None, None, 0, None) == hcsa.DLLM_ERR_INVALID_ARG
+    # a long kept list on few (sequence, head) pairs is split into chunks and needs partial-result space
+    b.batch, b.total_kv, b.max_kv = 1, 9000, 9000
+    need = hcsa.lib().dllm_hcsa_attend_workspace(ctypes.byref(b), 4000)
+    assert need > 0
+    assert attend_status(b, total_k=4000, max_k=4000, ws=None) == hcsa.DLLM_ERR_WORKSPACE
+    assert attend_status(b, total_k=4000, max_k=4000, ws_bytes=need - 1) == hcsa.DLLM_ERR_WORKSPACE
+
+
+def test_python_struct_matches_the_header_layout(tmp_path):
+    """Compile the header with gcc (as C99) and compare sizeof / offsetof with the ctypes mirror."""
+    import subprocess
+    fields = [f for f, _ in hcsa.DllmBatch._fields_]
+    src = tmp_path / "layout.c"
+    prints = "\n".join(f'  printf("{f} %zu\\n", offsetof(dllm_batch, {f}));' for f in fields)
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "dllm_hcsa.h"\nint main(void) {\n'
+                   '  printf("sizeof %zu\\n", sizeof(dllm_batch));\n' + prints + "\n  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    out = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    assert int(out["sizeof"]) == ctypes.sizeof(hcsa.DllmBatch)
+    for f in fields:
+        assert int(out[f]) == getattr(hcsa.DllmBatch, f).offset, f

@@ -1,0 +1,273 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Indices must match bit for bit; outputs within 1e-5 (fp32) / 2e-2 (bf16) absolute.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_17077_amd import hcsa, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2}
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def oracle_select(w, pool_w=1):
+    return oracle.select(synth.to_bits(w.q), synth.to_bits(w.k), w.cu_q, w.cu_kv, w.cu_k, pool_w)
+
+
+def oracle_attend(w, idx):
+    return oracle.attend(synth.to_bits(w.q), synth.to_bits(w.k), synth.to_bits(w.v), w.cu_q, w.cu_kv, idx, w.cu_k,
+                         w.seq_mode, w.softmax_scale)
+
+
+def check_select(w, pool_w=1, name=""):
+    say(f"select {name or w.name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} "
+        f"D={w.head_dim} maxL={int(w.kv_lens.max())} pool_w={pool_w}")
+    dw = hcsa.DeviceWorkload(w)
+    dw.idx.fill_(-7)
+    dw.select(pool_w)
+    torch.cuda.synchronize()
+    got = dw.idx.cpu().numpy()
+    ref = oracle_select(w, pool_w)
+    if not np.array_equal(got, ref):
+        bad = np.argwhere(got != ref)
+        h, t = bad[0]
+        raise AssertionError(f"{len(bad)} of {ref.size} indices differ; first at head {h}, slot {t}: "
+                             f"gpu {got[h, t]} oracle {ref[h, t]}")
+    return dw, ref
+
+
+def check_attend(w, idx, name="", dw=None):
+    say(f"attend {name or w.name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} "
+        f"D={w.head_dim} maxk={int(w.keep.max())} maxq={int(w.q_lens.max())}")
+    dw = dw or hcsa.DeviceWorkload(w)
+    dw.o.fill_(float("nan"))
+    dw.attend(torch.from_numpy(np.ascontiguousarray(idx)).to(dw.device))
+    torch.cuda.synchronize()
+    got = dw.o.float().cpu().numpy().astype(np.float64)
+    ref = oracle_attend(w, idx)
+    err = np.abs(got - ref)
+    assert np.isfinite(got).all(), "non-finite output"
+    assert err.max() <= TOL[w.dtype], f"max abs error {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+    return float(err.max())
+
+
+def custom(seed, dtype, Hq, Hkv, D, lens, qlens, keep, mode=None, salient=0.0):
+    return synth.make_workload(f"custom{seed}", synth.SEED_BASE + 1000 + seed, dtype, Hq, Hkv, D, lens, qlens, keep,
+                               seq_mode=mode, salient_frac=salient)
+
+
+# ------------------------------------------------------------------ selection
+
+@pytest.mark.parametrize("c", [1, 2])
+def test_select_small_configs(c):
+    check_select(synth.config(c))
+
+
+def test_select_config3_full():
+    check_select(synth.config(3))
+
+
+def test_select_config5_gqa_full():
+    check_select(synth.config(5))
+
+
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 128), (torch.float32, 64)])
+def test_select_ragged_lengths(dtype, D):
+    lens = [1, 63, 65, 257, 1000, 64, 300]
+    keep = [1, 10, 65, 100, 999, 64, 0]          # k == L, k == 1 and a skipped sequence included
+    w = custom(1, dtype, 4, 2, D, lens, [32, 1, 7, 33, 32, 32, 32], keep)
+    dw, ref = check_select(w)
+    # the skipped sequence has no slots; nothing outside [0, total_k) exists to be clobbered
+    assert dw.idx.shape[1] == sum(keep)
+
+
+def test_select_forced_ties_and_zero_queries():
+    w = custom(2, torch.bfloat16, 4, 4, 128, [500, 200], [32, 32], [50, 199])
+    # duplicate rows: bit-equal scores, lower position must win
+    w.k[100:200] = w.k[0:100]
+    w.k[520:560] = w.k[500:540]
+    check_select(w, name="duplicated rows")
+    w.q.zero_()
+    dw, ref = check_select(w, name="zero queries")
+    assert np.array_equal(ref[:, :50], np.tile(np.arange(50), (4, 1)))
+
+
+@pytest.mark.parametrize("pool_w", [3, 5])
+def test_select_with_pooling(pool_w):
+    w = custom(3, torch.bfloat16, 8, 2, 128, [700, 33, 2, 1500], [32, 32, 32, 32], [350, 5, 1, 150])
+    check_select(w, pool_w=pool_w)
+
+
+def test_select_maximum_lengths():
+    w = custom(4, torch.bfloat16, 2, 1, 64, [32768, 5], [32, 32], [3000, 2])
+    check_select(w)
+    w2 = custom(5, torch.bfloat16, 2, 1, 64, [16384], [32], [8000])
+    check_select(w2, pool_w=3)
+
+
+def test_select_strided_inputs():
+    """q/k/v as views into one fused QKV activation, the layout a model layer would hand over."""
+    Hq, Hkv, D, L = 8, 2, 128, 777
+    w = custom(6, torch.bfloat16, Hq, Hkv, D, [L], [L], [100])
+    fused = torch.zeros((L, Hq + 2 * Hkv, D), dtype=torch.bfloat16, device="cuda:0")
+    fused[:, :Hq] = w.q.cuda(); fused[:, Hq:Hq + Hkv] = w.k.cuda(); fused[:, Hq + Hkv:] = w.v.cuda()
+    q, k, v = fused[-32:, :Hq], fused[:, Hq:Hq + Hkv], fused[:, Hq + Hkv:]
+    w.q = w.q[-32:].contiguous()
+    w.cu_q = np.array([0, 32], np.int32)
+    cu_q = torch.tensor([0, 32], dtype=torch.int32, device="cuda:0")
+    cu_kv = torch.tensor([0, L], dtype=torch.int32, device="cuda:0")
+    cu_k = torch.tensor([0, 100], dtype=torch.int32, device="cuda:0")
+    batch = hcsa.make_batch(q, k, v, cu_q, cu_kv, 32, L, w.softmax_scale)
+    idx = torch.empty((Hq, 100), dtype=torch.int32, device="cuda:0")
+    hcsa.dllm_hcsa_select(batch, cu_k, 100, 100, idx)
+    ref = oracle_select(w)
+    assert np.array_equal(idx.cpu().numpy(), ref)
+    o = torch.empty((32, Hq, D), dtype=torch.bfloat16, device="cuda:0")
+    hcsa.dllm_hcsa_attend(batch, idx, cu_k, 100, 100, None, o)
+    err = np.abs(o.float().cpu().numpy() - oracle_attend(w, ref)).max()
+    assert err <= 2e-2
+
+
+# ------------------------------------------------------------------ attention over kept rows
+
+@pytest.mark.parametrize("c", [1, 2])
+def test_attend_small_configs(c):
+    w = synth.config(c)
+    check_attend(w, oracle_select(w))
+
+
+def test_attend_config3_full():
+    w = synth.config(3)
+    check_attend(w, oracle_select(w))
+
+
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)])
+def test_attend_ragged_keep_and_query_counts(dtype, D):
+    lens = [40, 300, 65, 1000, 129, 77]
+    keep = [1, 33, 65, 517, 0, 77]               # k == 1, k == L, nothing kept, several tiles + ragged tail
+    qlens = [1, 7, 33, 32, 32, 70]
+    w = custom(7, dtype, 4, 2, D, lens, qlens, keep)
+    idx = oracle_select(w)
+    check_attend(w, idx)
+    # k == 1 returns that V row exactly (bf16 in, bf16 out: no rounding at all)
+    dw = hcsa.DeviceWorkload(w)
+    dw.attend(torch.from_numpy(idx).cuda())
+    row = int(idx[0, 0])
+    assert torch.equal(dw.o[0, 0].cpu(), w.v[row, 0])
+
+
+def test_attend_unsorted_and_repeated_indices():
+    w = custom(8, torch.bfloat16, 4, 4, 128, [600, 90], [32, 32], [200, 90])
+    rng = np.random.default_rng(8)
+    idx = np.concatenate([rng.integers(0, 600, size=(4, 200)), rng.integers(0, 90, size=(4, 90))], axis=1).astype(np.int32)
+    check_attend(w, idx)
+
+
+def test_attend_chunked_long_keep_lists():
+    """Few (sequence, head) pairs with long kept lists are split over workgroups and merged."""
+    w = custom(9, torch.bfloat16, 2, 1, 128, [4096, 700], [32, 32], [3000, 100], salient=0.05)
+    dw = hcsa.DeviceWorkload(w)
+    assert hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k) > 0
+    check_attend(w, oracle_select(w), dw=dw)
+    w2 = custom(10, torch.bfloat16, 2, 2, 64, [2048], [45], [2048])
+    check_attend(w2, oracle_select(w2))
+
+
+def test_attend_keep_all_equals_dense_entry_point():
+    w = custom(11, torch.bfloat16, 4, 2, 128, [333, 64], [32, 20], [333, 64])
+    idx = oracle_select(w)
+    dw = hcsa.DeviceWorkload(w)
+    dw.attend(torch.from_numpy(idx).cuda())
+    sparse = dw.o.float().clone()
+    dw.o.zero_()
+    dw.dense_refresh()
+    assert (sparse - dw.o.float()).abs().max().item() <= 2e-2
+
+
+def test_select_then_attend_end_to_end_gpu_indices():
+    w = synth.config(3, scale_down=4)
+    dw, ref = check_select(w)
+    dw.attend()
+    torch.cuda.synchronize()
+    err = np.abs(dw.o.float().cpu().numpy() - oracle_attend(w, ref)).max()
+    assert err <= 2e-2
+
+
+# ------------------------------------------------------------------ dense and mixed
+
+def test_dense_small_and_ragged():
+    w = custom(12, torch.bfloat16, 4, 2, 128, [100, 129, 64, 1, 300], [100, 5, 64, 3, 257], [0] * 5,
+               mode=np.ones(5, np.uint8))
+    check_attend(w, np.zeros((4, 0), np.int32), name="dense via attend")
+    dw = hcsa.DeviceWorkload(w)
+    dw.o.fill_(float("nan"))
+    dw.dense_refresh()
+    err = np.abs(dw.o.float().cpu().numpy() - oracle_attend(w, np.zeros((4, 0), np.int32))).max()
+    assert err <= 2e-2
+    for dtype, D in ((torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)):
+        w = custom(13, dtype, 4, 4, D, [70, 200], [70, 9], [0, 0], mode=np.ones(2, np.uint8))
+        check_attend(w, np.zeros((4, 0), np.int32), name=f"dense {dtype} D={D}")
+
+
+def test_dense_config4_scaled():
+    w = synth.config(4, scale_down=8)
+    check_attend(w, np.zeros((32, 0), np.int32))
+
+
+def test_mixed_batch_scaled_config5():
+    w = synth.config(5, scale_down=16)
+    dw, ref = check_select(w)
+    check_attend(w, ref, dw=dw)
+
+
+def sample_rows(w, rows_per_seq, seed):
+    """Sub-workload with a few query rows of every sequence (all heads, full K/V): the oracle can
+    evaluate these one by one at full benchmark size."""
+    rng = np.random.default_rng(seed)
+    picks, qparts = [], []
+    for b in range(w.batch):
+        n = int(w.q_lens[b])
+        r = np.sort(rng.choice(n, size=min(n, rows_per_seq), replace=False)) + int(w.cu_q[b])
+        picks.append(r)
+        qparts.append(w.q[torch.from_numpy(r)])
+    sub = synth.Workload(w.name + "_sampled", w.dtype, w.n_q_heads, w.n_kv_heads, w.head_dim, torch.cat(qparts), w.k,
+                         w.v, np.concatenate([[0], np.cumsum([len(p) for p in picks])]).astype(np.int32), w.cu_kv,
+                         w.cu_k, w.seq_mode, w.softmax_scale)
+    return sub, np.concatenate(picks)
+
+
+def test_dense_config4_full_size_sampled_rows():
+    w = synth.config(4)
+    dw = hcsa.DeviceWorkload(w)
+    say("dense config 4 full size")
+    dw.o.fill_(float("nan"))
+    dw.dense_refresh()
+    torch.cuda.synchronize()
+    assert torch.isfinite(dw.o.float()).all()
+    sub, rows = sample_rows(w, 6, 44)
+    ref = oracle_attend(sub, np.zeros((w.n_q_heads, 0), np.int32))
+    got = dw.o[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+    assert np.abs(got - ref).max() <= 2e-2
+
+
+def test_mixed_config5_full_size():
+    w = synth.config(5)
+    dw, ref = check_select(w)
+    say("attend config 5 full size (mixed, one call)")
+    dw.o.fill_(float("nan"))
+    dw.attend()
+    torch.cuda.synchronize()
+    assert torch.isfinite(dw.o.float()).all()
+    sub, rows = sample_rows(w, 4, 55)
+    want = oracle_attend(sub, ref)
+    got = dw.o[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+    assert np.abs(got - want).max() <= 2e-2
