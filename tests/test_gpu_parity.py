@@ -93,8 +93,8 @@ def test_select_ragged_lengths(dtype, D):
 def test_select_forced_ties_and_zero_queries():
     w = custom(2, torch.bfloat16, 4, 4, 128, [500, 200], [32, 32], [50, 199])
     # duplicate rows: bit-equal scores, lower position must win
-    w.k[100:200] = w.k[0:100]
-    w.k[520:560] = w.k[500:540]
+    w.k[100:200] = w.k[0:100].clone()
+    w.k[520:560] = w.k[500:540].clone()
     check_select(w, name="duplicated rows")
     w.q.zero_()
     dw, ref = check_select(w, name="zero queries")
