@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the Head-Centric Sparse Attention hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over resident synthetic inputs:
+    select  + attend   on the batched Reuse workload   (16 seqs, KV 512..4096, keep 10..50 %)
+    dense Refresh      on the Refresh workload          (8 x L=2048, 32 heads x 128)
+    select  + attend   on the mixed GQA burst           (24 Reuse + 8 Refresh sequences in one call)
+All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
+stream it is launched on; rates are algorithmic bytes (or flops) divided by the mean call duration.
+
+Prints ONE JSON line.  `value` is the Reuse sparse-attention rate in GB/s of algorithmic bytes
+(the headline of the metric); the Refresh TFLOP/s and the other calls are reported beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
+
+# HBM bytes per launch from rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, scaled by the same
+# counters over a plain copy of known size); see profiles/.  None where not collected.
+TRAFFIC_BYTES = {
+    "attend_dense_bf16_kernel": None,
+    "attend_sparse_bf16_kernel": None,
+    "score_kernel": None,
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device copy (reference launch for scaling rocprofv3 byte counters)")
+    ap.add_argument("--only", choices=["all", "reuse", "refresh", "mixed"], default="all",
+                    help="restrict the step to one workload (for profiling runs)")
+    return ap.parse_args()
+
+
+class Timed:
+    """A library call timed with an event pair on the current stream, once per step."""
+
+    def __init__(self, name, fn):
+        import torch
+        self.name, self.fn, self.pairs, self.torch = name, fn, [], torch
+
+    def __call__(self, record):
+        if not record:
+            self.fn()
+            return
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        self.fn()
+        b.record()
+        self.pairs.append((a, b))
+
+    def ms(self):
+        t = [a.elapsed_time(b) for a, b in self.pairs]
+        return (sum(t) / len(t), min(t)) if t else (float("nan"), float("nan"))
+
+
+def cpu_baseline(w3, w4):
+    """The oracle as it stands, timed on this host: the full Reuse workload (selection and attention)
+    and a bounded sample of Refresh query rows."""
+    import numpy as np
+    import oracle
+    from paper_2512_17077_amd import synth
+    q, k, v = synth.to_bits(w3.q), synth.to_bits(w3.k), synth.to_bits(w3.v)
+    t0 = time.perf_counter()
+    idx = oracle.select(q, k, w3.cu_q, w3.cu_kv, w3.cu_k)
+    t1 = time.perf_counter()
+    oracle.attend(q, k, v, w3.cu_q, w3.cu_kv, idx, w3.cu_k, None, w3.softmax_scale)
+    t2 = time.perf_counter()
+    # Refresh sample: 8 query rows of the first sequence, all heads, against its full K/V
+    n = 8
+    L = int(w4.kv_lens[0])
+    sub_q = synth.to_bits(w4.q[:n])
+    sub_k, sub_v = synth.to_bits(w4.k[:L]), synth.to_bits(w4.v[:L])
+    t3 = time.perf_counter()
+    oracle.attend(sub_q, sub_k, sub_v, np.array([0, n], np.int32), np.array([0, L], np.int32), None, None,
+                  np.ones(1, np.uint8), w4.softmax_scale)
+    t4 = time.perf_counter()
+    dense_flops = 4.0 * n * L * w4.head_dim * w4.n_q_heads
+    return {
+        "value": w3.attend_sparse_bytes() / (t2 - t1) / 1e9,
+        "unit": "GB/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"full Reuse workload {w3.name}: attend {t2 - t1:.2f} s, select {t1 - t0:.2f} s; "
+                  f"Refresh: {n} query rows x {w4.n_q_heads} heads of one L={L} sequence {t4 - t3:.2f} s",
+        "select_gbps": w3.select_bytes() / (t1 - t0) / 1e9,
+        "refresh_tflops": dense_flops / (t4 - t3) / 1e12,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); "
+              "the path shards by sequence or by head with no exchange, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2512_17077_amd import hcsa, synth
+    hcsa.lib()   # raises if the HIP library is not built: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+
+    w3, w4, w5 = synth.config(3), synth.config(4), synth.config(5)
+    d3, d4, d5 = (hcsa.DeviceWorkload(w, "cuda:0") for w in (w3, w4, w5))
+
+    def ws(nbytes):
+        return torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
+    ws3s = ws(hcsa.dllm_hcsa_select_workspace(d3.batch, d3.max_k))
+    ws3a = ws(hcsa.dllm_hcsa_attend_workspace(d3.batch, d3.max_k))
+    ws5s = ws(hcsa.dllm_hcsa_select_workspace(d5.batch, d5.max_k))
+    ws5a = ws(hcsa.dllm_hcsa_attend_workspace(d5.batch, d5.max_k))
+
+    calls = []
+    if args.only in ("all", "reuse"):
+        calls += [Timed("select_reuse", lambda: d3.select(workspace=ws3s)),
+                  Timed("attend_reuse", lambda: d3.attend(workspace=ws3a))]
+    if args.only in ("all", "refresh"):
+        calls += [Timed("dense_refresh", lambda: d4.dense_refresh())]
+    if args.only in ("all", "mixed"):
+        calls += [Timed("select_mixed", lambda: d5.select(workspace=ws5s)),
+                  Timed("attend_mixed", lambda: d5.attend(workspace=ws5a))]
+
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        for c in calls:
+            c(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for c in calls:
+            c(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    T = {c.name: c.ms() for c in calls}
+
+    def rate_gbps(nbytes, name):
+        return nbytes / (T[name][0] * 1e-3) / 1e9 if name in T else None
+
+    def rate_tflops(flops, name):
+        return flops / (T[name][0] * 1e-3) / 1e12 if name in T else None
+
+    reuse_gbps = rate_gbps(w3.attend_sparse_bytes(), "attend_reuse")
+    select_gbps = rate_gbps(w3.select_bytes(), "select_reuse")
+    refresh_tflops = rate_tflops(w4.attend_dense_flops(), "dense_refresh")
+    mixed_sel_gbps = rate_gbps(w5.select_bytes(), "select_mixed")
+
+    def roof(bound, achieved, peak, unit, kernel, algorithmic):
+        if achieved is None:
+            return None
+        return {"bound": bound, "kernel": kernel, "achieved": achieved, "peak": peak, "unit": unit,
+                "frac": achieved / peak, "algorithmic_per_launch": algorithmic,
+                "traffic": TRAFFIC_BYTES.get(kernel)}
+
+    out = {
+        "metric": "Reuse sparse-attn HBM GB/s (% of peak) + Refresh attn TFLOP/s, 1 MI355X",
+        "value": reuse_gbps if reuse_gbps is not None else refresh_tflops,
+        "unit": "GB/s" if reuse_gbps is not None else "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "c3_batched_reuse (value: Reuse attend) + c4_refresh_dense (Refresh TFLOP/s) + "
+                        "c5_mixed_burst_gqa (one-call mixed dispatch)",
+            "step": [c.name for c in calls],
+            "reuse": {"batch": w3.batch, "heads": w3.n_q_heads, "head_dim": w3.head_dim, "block": 32,
+                      "sum_kv": w3.total_kv, "sum_keep": w3.total_k,
+                      "attend_bytes": w3.attend_sparse_bytes(), "select_bytes": w3.select_bytes()},
+            "refresh": {"batch": w4.batch, "heads": w4.n_q_heads, "head_dim": w4.head_dim,
+                        "L": int(w4.kv_lens[0]), "flops": w4.attend_dense_flops()},
+            "mixed": {"batch": w5.batch, "q_heads": w5.n_q_heads, "kv_heads": w5.n_kv_heads,
+                      "reuse_seqs": int((w5.seq_mode == 0).sum()), "refresh_seqs": int((w5.seq_mode == 1).sum()),
+                      "sparse_bytes": w5.attend_sparse_bytes(), "dense_flops": w5.attend_dense_flops()},
+        },
+        "reuse_attend_gbps": reuse_gbps,
+        "reuse_attend_pct_of_hbm_peak": None if reuse_gbps is None else 100.0 * reuse_gbps / HBM_PEAK_GBPS,
+        "reuse_select_gbps": select_gbps,
+        "refresh_tflops": refresh_tflops,
+        "refresh_pct_of_mfma_peak": None if refresh_tflops is None else 100.0 * refresh_tflops / MFMA_BF16_PEAK_TFLOPS,
+        "mixed_select_gbps": mixed_sel_gbps,
+        "call_ms_mean_min": {k: [round(v[0], 5), round(v[1], 5)] for k, v in T.items()},
+        # the kernel that dominates the step's time is the dense Refresh kernel (one launch per call)
+        "roofline": roof("mfma", refresh_tflops, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "attend_dense_bf16_kernel",
+                         w4.attend_dense_flops()),
+        "roofline_reuse": roof("hbm", reuse_gbps, HBM_PEAK_GBPS, "GB/s", "attend_sparse_bf16_kernel",
+                               w3.attend_sparse_bytes()),
+        "roofline_select": roof("hbm", select_gbps, HBM_PEAK_GBPS, "GB/s", "score_kernel", w3.select_bytes()),
+        "peaks": {"hbm_GBps": HBM_PEAK_GBPS, "mfma_bf16_dense_TFLOPs": MFMA_BF16_PEAK_TFLOPS},
+        "paper_context": "dLLM-Serve reports end-to-end serving gains only (1.61-1.81x on RTX 4090, "
+                         "1.60-1.74x on L40S); no kernel-level number exists for this path",
+    }
+    if "attend_mixed" in T:
+        bound_ms = max(w5.attend_dense_flops() / (MFMA_BF16_PEAK_TFLOPS * 1e12),
+                       w5.attend_sparse_bytes() / (HBM_PEAK_GBPS * 1e9)) * 1e3
+        out["mixed_attend"] = {"ms": T["attend_mixed"][0], "lower_bound_ms": bound_ms,
+                               "dense_tflops_if_alone": w5.attend_dense_flops() / (T["attend_mixed"][0] * 1e-3) / 1e12}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w3, w4)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

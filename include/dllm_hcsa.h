@@ -77,7 +77,7 @@ typedef struct {
   const int32_t *cu_kv;        /* device, [batch+1] */
   int32_t total_q, total_kv;   /* cu_q[batch], cu_kv[batch] */
   int32_t max_q, max_kv;       /* upper bounds on per-sequence query count / KV length */
-  float softmax_scale;         /* multiplies q.k before the softmax; 1/sqrt(D) in the paper */
+  float softmax_scale;         /* multiplies q.k before the softmax; finite, > 0; 1/sqrt(D) in the paper */
 } dllm_batch;
 
 /*

@@ -47,7 +47,8 @@ dllm_status check_batch(const dllm_batch* b, dllm::Shape* out) {
     return fail(DLLM_ERR_INVALID_ARG, "strides must be multiples of 16 bytes");
   if (!aligned16(b->q) || !aligned16(b->k) || !aligned16(b->v))
     return fail(DLLM_ERR_INVALID_ARG, "q, k and v must be 16-byte aligned");
-  if (!std::isfinite(b->softmax_scale)) return fail(DLLM_ERR_INVALID_ARG, "softmax_scale is not finite");
+  if (!std::isfinite(b->softmax_scale) || !(b->softmax_scale > 0.0f))
+    return fail(DLLM_ERR_INVALID_ARG, "softmax_scale must be finite and positive");
   out->batch = b->batch;
   out->hq = b->n_q_heads;
   out->hkv = b->n_kv_heads;

@@ -7,43 +7,35 @@
 //   gather   idx -> row addresses; 16-byte loads with a row's chunks in neighbouring lanes (whole
 //            256-byte rows per 16 lanes), prefetched one tile ahead into registers
 //   stage    registers -> the wave's private LDS tile, XOR-swizzled by row
-//   S^T      = K_tile (32 keys x D) * Q^T (D x 32 queries): v_mfma_f32_32x32x16_bf16, A from LDS, B = Q in registers
-//   softmax  online, base 2, per query column: 16 registers in-lane plus one cross-half exchange
-//   O^T     += V_tile^T (D x 32 keys) * P^T: P^T is the S^T accumulator re-used in place as B operand,
-//            V^T gathered from the LDS tile in the matching key order
+//   S^T      = K_tile (32 keys x D) * Q^T (D x 32 queries): A by ds_read_b128, B = Q in registers
+//   softmax  online, base 2, lazily rescaled, per query column
+//   O^T     += V_tile^T * P^T: A by ds_read_b64_tr_b16, B = the S^T accumulators in place
 // After the loop the four waves merge (m, l, O) through LDS.  A (sequence, head) whose kept rows fit
 // one chunk writes O directly; otherwise chunks write fp32 partials and a small kernel merges them.
-#include "common.h"
+#include "attn_tile.h"
 
 namespace dllm {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
 constexpr int kTile = 32;        // kept rows per wave tile
 constexpr int kWaves = 4;
-constexpr float kLog2e = 1.4426950408889634f;
-
-template <int CH>
-__device__ __forceinline__ int swz_rows(int row) {
-  constexpr int rows_per_line = CH >= 16 ? 1 : 16 / CH;
-  return (row / rows_per_line) & (CH - 1);
-}
+constexpr float kLazyStepS = 8.0f;
 
 template <int D>
-__global__ __launch_bounds__(kWaves * 64) void attend_sparse_bf16_kernel(
+__global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cu_k, int32_t total_k, const uint8_t* __restrict__ seq_mode,
     uint16_t* __restrict__ o, float* __restrict__ po, float* __restrict__ pm, float* __restrict__ pl,
     int32_t chunk_rows, Shape s) {
-  constexpr int CH = D / 8;          // 16-byte chunks per row
+  constexpr int CH = D / 8;             // 16-byte chunks per row
+  constexpr int ROWB = 2 * D;
+  constexpr int TILEB = kTile * ROWB;
   constexpr int NLD = kTile * CH / 64;  // 16-byte loads per lane per tile and tensor
-  constexpr int NT = D / 16;         // MFMA steps along head_dim
-  constexpr int NDB = D / 32;        // 32-wide blocks of head_dim in the output
+  constexpr int NT = D / 16;            // MFMA steps along head_dim
+  constexpr int NDB = D / 32;           // 32-wide blocks of head_dim in the output
 
-  // per wave: K tile then V tile (kTile*CH uint4 each); reused as fp32 merge space afterwards
-  __shared__ uint4 lds[kWaves][2 * kTile * CH];
+  // per wave: K tile then V tile; reused as fp32 merge space afterwards
+  __shared__ __attribute__((aligned(16))) char lds[kWaves][2 * TILEB];
   __shared__ float sm_m[kWaves][32], sm_l[kWaves][32];
 
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -71,63 +63,69 @@ __global__ __launch_bounds__(kWaves * 64) void attend_sparse_bf16_kernel(
   const int64_t pitch = s.kv_tok * 2;
   const float zscale = s.scale * kLog2e;
   const int ntiles = (c1 - c0 + kTile - 1) / kTile;
-  uint4* ktile = lds[wave];
-  uint4* vtile = lds[wave] + kTile * CH;
-  const uint16_t* vt16 = reinterpret_cast<const uint16_t*>(vtile);
+  char* ktile = lds[wave];
+  char* vtile = lds[wave] + TILEB;
+
+  KAddr<D> ka;
+  ka.init(lane);
+  VtAddr<D> vt;
+  vt.init(lane);
+  int woff[NLD];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int f = i * 64 + lane;
+    woff[i] = tile_off<D>(f / CH, f % CH);
+  }
+  const int coff = (lane % CH) * 16;   // this lane's byte offset inside a gathered row
 
   for (int qt = 0; qt * 32 < nq; ++qt) {
     // Q^T operand: lane (col = query, hf) holds Q[query][16t + 8hf .. +8) for every step t
-    uint4 qreg[NT];
+    v4u qreg[NT];
     {
       const int qi = qt * 32 + col;
       const uint16_t* qp = q + int64_t(q0 + qi) * s.q_tok + int64_t(h) * s.q_head;
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        qreg[t] = make_uint4(0, 0, 0, 0);
-        if (qi < nq) qreg[t] = *reinterpret_cast<const uint4*>(qp + 16 * t + 8 * hf);
+        qreg[t] = v4u{0u, 0u, 0u, 0u};
+        if (qi < nq) qreg[t] = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
       }
     }
-    float m = -INFINITY, l = 0.0f;
+    float m_used = -INFINITY, lsum = 0.0f;
     f32x16 acc[NDB];
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[db][i] = 0.0f;
 
-    uint4 kr[NLD], vr[NLD];
-    auto fetch = [&](int tile, int my_row) {
-      // my_row: this lane's kept-row id for tile row (lane & 31), or -1 past the end
-      (void)tile;
+    v4u kr[NLD], vr[NLD];
+    // my_row: this lane's kept-row id for tile row (lane & 31); rows past the end repeat a valid row
+    // and are masked out of the softmax below
+    auto fetch = [&](int my_row) {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int f = i * 64 + lane, row = f / CH, c = f % CH;
-        const int r = __shfl(my_row, row);
-        kr[i] = make_uint4(0, 0, 0, 0);
-        vr[i] = make_uint4(0, 0, 0, 0);
-        if (r >= 0) {
-          kr[i] = *reinterpret_cast<const uint4*>(kbase + r * pitch + c * 16);
-          vr[i] = *reinterpret_cast<const uint4*>(vbase + r * pitch + c * 16);
-        }
+        const int row = (i * 64 + lane) / CH;
+        const int64_t r = __shfl(my_row, row);
+        kr[i] = *reinterpret_cast<const v4u*>(kbase + r * pitch + coff);
+        vr[i] = *reinterpret_cast<const v4u*>(vbase + r * pitch + coff);
       }
     };
     auto row_of = [&](int tile) -> int {
-      const int t = c0 + tile * kTile + col;
-      return (tile < ntiles && t < c1) ? rows[t] : -1;
+      const int t = min(c0 + tile * kTile + col, c1 - 1);
+      return tile < ntiles ? rows[t] : 0;
     };
 
     int tile = wave;
     int row_next = row_of(tile);
-    if (tile < ntiles) fetch(tile, row_next);
+    if (tile < ntiles) fetch(row_next);
     row_next = row_of(tile + kWaves);
 
     for (; tile < ntiles; tile += kWaves) {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int f = i * 64 + lane, row = f / CH, c = f % CH;
-        ktile[row * CH + (c ^ swz_rows<CH>(row))] = kr[i];
-        vtile[row * CH + (c ^ swz_rows<CH>(row))] = vr[i];
+        *reinterpret_cast<v4u*>(ktile + woff[i]) = kr[i];
+        *reinterpret_cast<v4u*>(vtile + woff[i]) = vr[i];
       }
-      if (tile + kWaves < ntiles) fetch(tile + kWaves, row_next);
+      if (tile + kWaves < ntiles) fetch(row_next);
       row_next = row_of(tile + 2 * kWaves);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -138,69 +136,61 @@ __global__ __launch_bounds__(kWaves * 64) void attend_sparse_bf16_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) st[i] = 0.0f;
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        const uint4 a = ktile[col * CH + ((2 * t + hf) ^ swz_rows<CH>(col))];
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                     __builtin_bit_cast(bf16x8, qreg[t]), st, 0, 0, 0);
-      }
-      // accumulator register i of lane (col, hf) is key 8*(i/4) + 4*hf + i%4 of the tile
-      const int nvalid = c1 - (c0 + tile * kTile);
-      float mloc = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = 8 * (i / 4) + 4 * hf + (i % 4);
-        st[i] = key < nvalid ? st[i] * zscale : -INFINITY;
-        mloc = fmaxf(mloc, st[i]);
-      }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-      const float m_new = fmaxf(m, mloc);
-      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-      float psum = 0.0f;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        st[i] = __builtin_amdgcn_exp2f(st[i] - m_new);
-        psum += st[i];
-      }
-      l = l * alpha + psum;
-      m = m_new;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+      for (int t = 0; t < NT; ++t)
+        st = mfma_bf16(*reinterpret_cast<const v4u*>(ktile + ka.off(t)), qreg[t], st);
 
-      // O^T += V^T P^T, 16 keys per step; slot sl of lane half hf is key 16u + 8*(sl/4) + 4*hf + sl%4
+      const int nvalid = c1 - (c0 + tile * kTile);
+      if (nvalid < kTile) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        uint4 pb;
-        pb.x = pack_bf16x2(st[8 * u + 0], st[8 * u + 1]);
-        pb.y = pack_bf16x2(st[8 * u + 2], st[8 * u + 3]);
-        pb.z = pack_bf16x2(st[8 * u + 4], st[8 * u + 5]);
-        pb.w = pack_bf16x2(st[8 * u + 6], st[8 * u + 7]);
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const int d = db * 32 + col;
-          uint32_t w[4];
-#pragma unroll
-          for (int sp = 0; sp < 4; ++sp) {
-            const int s0 = 2 * sp, s1 = 2 * sp + 1;
-            const int key0 = 16 * u + 8 * (s0 / 4) + 4 * hf + (s0 % 4);
-            const int key1 = 16 * u + 8 * (s1 / 4) + 4 * hf + (s1 % 4);
-            const uint32_t lo = vt16[(key0 * CH + ((d >> 3) ^ swz_rows<CH>(key0))) * 8 + (d & 7)];
-            const uint32_t hi = vt16[(key1 * CH + ((d >> 3) ^ swz_rows<CH>(key1))) * 8 + (d & 7)];
-            w[sp] = lo | (hi << 16);
-          }
-          const uint4 a = make_uint4(w[0], w[1], w[2], w[3]);
-          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                          __builtin_bit_cast(bf16x8, pb), acc[db], 0, 0, 0);
+        for (int i = 0; i < 16; ++i) {
+          const int key = 8 * (i / 4) + 4 * hf + (i % 4);
+          if (key >= nvalid) st[i] = -INFINITY;
         }
       }
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, st[i]), st[i + 1]);
+      tmax = max_across_halves(tmax) * zscale;   // zscale >= 0
+      if (__builtin_amdgcn_ballot_w64(tmax > m_used + kLazyStepS) != 0) {
+        const float m_new = fmaxf(m_used, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m_used - m_new);   // first tile: exp2(-inf) = 0
+        m_used = m_new;
+        lsum *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+      }
+      const float neg_m = -m_used;
+      v4u pb[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * j], zscale, neg_m));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * j + 1], zscale, neg_m));
+          w[j] = cvt_pk_bf16(p0, p1);
+          lsum = add_pair_bf16(w[j], lsum);
+        }
+        pb[u] = v4u{w[0], w[1], w[2], w[3]};
+      }
+      // O^T += V^T P^T, 16 keys per step
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+          const v2u lo = lds_read_tr16(vtile + vt.off(0, db) + 16 * u * ROWB);
+          const v2u hi = lds_read_tr16(vtile + vt.off(1, db) + 16 * u * ROWB);
+          acc[db] = mfma_bf16(v4u{lo.x, lo.y, hi.x, hi.y}, pb[u], acc[db]);
+        }
       __builtin_amdgcn_wave_barrier();
     }
 
     // ---- merge the four waves' (m, l, O^T) through LDS
-    l += __shfl_xor(l, 32);
+    const float l = sum_across_halves(lsum);
     __syncthreads();                       // every wave is done with its tile buffers
-    if (hf == 0) { sm_m[wave][col] = m; sm_l[wave][col] = l; }
+    if (hf == 0) { sm_m[wave][col] = m_used; sm_l[wave][col] = l; }
     __syncthreads();
     float m_all = -INFINITY;
 #pragma unroll
@@ -208,8 +198,8 @@ __global__ __launch_bounds__(kWaves * 64) void attend_sparse_bf16_kernel(
     float l_all = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) l_all += sm_l[w][col] * __builtin_amdgcn_exp2f(sm_m[w][col] - m_all);
-    const float mine = __builtin_amdgcn_exp2f(m - m_all);   // 0 for a wave that saw no tile
-    float* mrg = reinterpret_cast<float*>(&lds[0][0]);      // [wave][db][reg][lane]
+    const float mine = __builtin_amdgcn_exp2f(m_used - m_all);   // 0 for a wave that saw no tile
+    float* mrg = reinterpret_cast<float*>(&lds[0][0]);           // [wave][db][reg][lane]
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -232,10 +222,10 @@ __global__ __launch_bounds__(kWaves * 64) void attend_sparse_bf16_kernel(
           uint16_t* op = o + (int64_t(q0 + qi) * s.hq + h) * D + db * 32 + 4 * hf;
 #pragma unroll
           for (int i4 = 0; i4 < 4; ++i4) {
-            uint2 w2;
-            w2.x = pack_bf16x2(outv[4 * i4 + 0] * inv, outv[4 * i4 + 1] * inv);
-            w2.y = pack_bf16x2(outv[4 * i4 + 2] * inv, outv[4 * i4 + 3] * inv);
-            *reinterpret_cast<uint2*>(op + 8 * i4) = w2;
+            v2u w2;
+            w2.x = cvt_pk_bf16(outv[4 * i4 + 0] * inv, outv[4 * i4 + 1] * inv);
+            w2.y = cvt_pk_bf16(outv[4 * i4 + 2] * inv, outv[4 * i4 + 3] * inv);
+            *reinterpret_cast<v2u*>(op + 8 * i4) = w2;
           }
         } else {
           const int64_t slot = (int64_t(chunk) * s.total_q + (q0 + qi)) * s.hq + h;
@@ -253,6 +243,8 @@ __global__ __launch_bounds__(kWaves * 64) void attend_sparse_bf16_kernel(
 }
 
 // Merge the chunk partials of every (sequence, head) that needed more than one chunk.
+// One workgroup per (head, sequence): 8 threads per query row, each owning D/8 output elements,
+// so all loads of a row are independent and issued together.
 template <int D>
 __global__ __launch_bounds__(256) void attend_sparse_combine_kernel(
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k, const uint8_t* __restrict__ seq_mode,
@@ -264,19 +256,30 @@ __global__ __launch_bounds__(256) void attend_sparse_combine_kernel(
   const int nch = (kb + chunk_rows - 1) / chunk_rows;
   if (nch <= 1) return;
   const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
-  constexpr int RPB = 256 / D;   // query rows per pass
-  const int d = threadIdx.x % D;
-  for (int i = threadIdx.x / D; i < nq; i += RPB) {
+  constexpr int EPT = D / 8;   // elements per thread
+  const int sub = threadIdx.x & 7;
+  for (int i = threadIdx.x >> 3; i < nq; i += 32) {
     float m_all = -INFINITY;
     for (int c = 0; c < nch; ++c) m_all = fmaxf(m_all, pm[(int64_t(c) * s.total_q + (q0 + i)) * s.hq + h]);
-    float l_all = 0.0f, a = 0.0f;
+    float l_all = 0.0f, a[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) a[e] = 0.0f;
     for (int c = 0; c < nch; ++c) {
       const int64_t slot = (int64_t(c) * s.total_q + (q0 + i)) * s.hq + h;
       const float w = __builtin_amdgcn_exp2f(pm[slot] - m_all);
       l_all += pl[slot] * w;
-      a += po[slot * D + d] * w;
+      const float4* src = reinterpret_cast<const float4*>(po + slot * D + sub * EPT);
+#pragma unroll
+      for (int e = 0; e < EPT / 4; ++e) {
+        const float4 x = src[e];
+        a[4 * e + 0] += x.x * w; a[4 * e + 1] += x.y * w; a[4 * e + 2] += x.z * w; a[4 * e + 3] += x.w * w;
+      }
     }
-    o[(int64_t(q0 + i) * s.hq + h) * D + d] = uint16_t(f32_to_bf16_bits(a / l_all));
+    const float inv = 1.0f / l_all;
+    uint16_t* op = o + (int64_t(q0 + i) * s.hq + h) * D + sub * EPT;
+#pragma unroll
+    for (int e = 0; e < EPT; e += 2)
+      *reinterpret_cast<uint32_t*>(op + e) = cvt_pk_bf16(a[e] * inv, a[e + 1] * inv);
   }
 }
 

@@ -9,6 +9,11 @@ namespace dllm {
 
 constexpr int kWave = 64;
 
+// 16 bytes as a native vector: loads and stores of it stay plain vector moves in every address
+// space, so register tiles built from it are always promoted out of private memory
+typedef __attribute__((ext_vector_type(4))) unsigned int v4u;
+typedef __attribute__((ext_vector_type(2))) unsigned int v2u;
+
 // Element strides and sizes every kernel needs; built once per call on the host.
 struct Shape {
   int32_t batch, hq, hkv, group, d;

@@ -31,7 +31,15 @@ __global__ void block_qsum_kernel(const T* __restrict__ q, const int32_t* __rest
   const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
   const T* p = q + int64_t(q0) * s.q_tok + int64_t(h) * s.q_head + d;
   float a = 0.0f;
-  for (int i = 0; i < nq; ++i) a = a + widen<T>(p + int64_t(i) * s.q_tok);
+  int i = 0;
+  for (; i + 16 <= nq; i += 16) {   // 16 independent loads in flight, then the adds in row order
+    float x[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x[j] = widen<T>(p + int64_t(i + j) * s.q_tok);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) a = a + x[j];
+  }
+  for (; i < nq; ++i) a = a + widen<T>(p + int64_t(i) * s.q_tok);
   qsum[(int64_t(b) * s.hq + h) * s.d + d] = a;
 }
 
@@ -46,72 +54,84 @@ __device__ __forceinline__ int swz(int row) {
   return (row / rows_per_line) & (CH - 1);
 }
 
-// ES: element bytes (2 = bf16, 4 = fp32); D: head_dim; GT: query heads scored per pass over the tile
+// ES: element bytes (2 = bf16, 4 = fp32); D: head_dim; GT: query heads scored per pass over the tile.
+// Each wave walks `tiles_per_wave` consecutive 64-row tiles; while it scores one tile out of LDS the
+// next tile's rows are already in flight into registers.
 template <int ES, int D, int GT>
 __global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
     const char* __restrict__ k, const float* __restrict__ qsum, const int32_t* __restrict__ cu_kv,
-    const int32_t* __restrict__ cu_k, float* __restrict__ scores, Shape s) {
+    const int32_t* __restrict__ cu_k, float* __restrict__ scores, int tiles_per_wave, Shape s) {
   constexpr int ROWB = D * ES;
   constexpr int CH = ROWB / 16;   // 16-byte chunks per row
   constexpr int EPC = 16 / ES;    // elements per chunk
-  __shared__ uint4 tile[kScoreWaves][64 * CH];
+  __shared__ v4u tile[kScoreWaves][64 * CH];
 
-  const int b = blockIdx.z, g = blockIdx.y;
+  // KV head is the fastest grid index: workgroups launched together read neighbouring 2*D-byte
+  // slices of the same token rows, which keeps the DRAM pages they open busy
+  const int b = blockIdx.z, g = blockIdx.x;
   if (cu_k[b + 1] == cu_k[b]) return;
   const int kv0 = cu_kv[b], L = cu_kv[b + 1] - kv0;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int r0 = blockIdx.x * kScoreRowsPerBlock + wave * 64;
-  if (r0 >= L) return;
-  const int nrows = min(64, L - r0);
-  const char* base = k + (int64_t(kv0 + r0) * s.kv_tok + int64_t(g) * s.kv_head) * ES;
+  const int first = (blockIdx.y * kScoreWaves + wave) * tiles_per_wave * 64;
+  if (first >= L) return;
+  const int ntiles = min(tiles_per_wave, (L - first + 63) / 64);
+  const char* base = k + (int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head) * ES + (lane % CH) * 16;
   const int64_t row_pitch = s.kv_tok * ES;
-
-  uint4 regs[CH];
-#pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int f = i * 64 + lane, row = f / CH, c = f % CH;
-    regs[i] = make_uint4(0, 0, 0, 0);
-    if (row < nrows) regs[i] = *reinterpret_cast<const uint4*>(base + row * row_pitch + c * 16);
-  }
-  uint4* mine = tile[wave];
-#pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int f = i * 64 + lane, row = f / CH, c = f % CH;
-    mine[row * CH + (c ^ swz<CH>(row))] = regs[i];
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
+  v4u* mine = tile[wave];
   const int sw = swz<CH>(lane);
-  for (int hh = 0; hh < s.group; hh += GT) {
-    const int h0 = g * s.group + hh;
-    const float* __restrict__ qs = qsum + (int64_t(b) * s.hq + h0) * D;
-    float acc[GT];
+
+  v4u regs[CH];
+  // rows past the end of the sequence re-read its last row; their scores are never stored
+  auto fetch = [&](int r0) {
 #pragma unroll
-    for (int t = 0; t < GT; ++t) acc[t] = 0.0f;
+    for (int i = 0; i < CH; ++i) {
+      const int row = min(r0 + (i * 64 + lane) / CH, L - 1);
+      regs[i] = *reinterpret_cast<const v4u*>(base + row * row_pitch);
+    }
+  };
+  fetch(first);
+  for (int it = 0; it < ntiles; ++it) {
+    const int r0 = first + it * 64;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const uint4 x = mine[lane * CH + (c ^ sw)];
-      float kv[EPC];
-      if constexpr (ES == 2) {
-        kv[0] = bf16_lo(x.x); kv[1] = bf16_hi(x.x); kv[2] = bf16_lo(x.y); kv[3] = bf16_hi(x.y);
-        kv[4] = bf16_lo(x.z); kv[5] = bf16_hi(x.z); kv[6] = bf16_lo(x.w); kv[7] = bf16_hi(x.w);
-      } else {
-        kv[0] = __uint_as_float(x.x); kv[1] = __uint_as_float(x.y);
-        kv[2] = __uint_as_float(x.z); kv[3] = __uint_as_float(x.w);
+    for (int i = 0; i < CH; ++i) {
+      const int f = i * 64 + lane, row = f / CH, c = f % CH;
+      mine[row * CH + (c ^ swz<CH>(row))] = regs[i];
+    }
+    if (it + 1 < ntiles) fetch(r0 + 64);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    for (int hh = 0; hh < s.group; hh += GT) {
+      const int h0 = g * s.group + hh;
+      const float* __restrict__ qs = qsum + (int64_t(b) * s.hq + h0) * D;
+      float acc[GT];
+#pragma unroll
+      for (int t = 0; t < GT; ++t) acc[t] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const v4u x = mine[lane * CH + (c ^ sw)];
+        float kv[EPC];
+        if constexpr (ES == 2) {
+          kv[0] = bf16_lo(x.x); kv[1] = bf16_hi(x.x); kv[2] = bf16_lo(x.y); kv[3] = bf16_hi(x.y);
+          kv[4] = bf16_lo(x.z); kv[5] = bf16_hi(x.z); kv[6] = bf16_lo(x.w); kv[7] = bf16_hi(x.w);
+        } else {
+          kv[0] = __uint_as_float(x.x); kv[1] = __uint_as_float(x.y);
+          kv[2] = __uint_as_float(x.z); kv[3] = __uint_as_float(x.w);
+        }
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+#pragma unroll
+          for (int t = 0; t < GT; ++t) acc[t] = __builtin_fmaf(qs[t * D + c * EPC + e], kv[e], acc[t]);
+        }
       }
+      if (r0 + lane < L) {
 #pragma unroll
-      for (int e = 0; e < EPC; ++e) {
-#pragma unroll
-        for (int t = 0; t < GT; ++t) acc[t] = __builtin_fmaf(qs[t * D + c * EPC + e], kv[e], acc[t]);
+        for (int t = 0; t < GT; ++t)
+          scores[int64_t(h0 + t) * s.total_kv + kv0 + r0 + lane] = acc[t] + 0.0f;
       }
     }
-    if (lane < nrows) {
-#pragma unroll
-      for (int t = 0; t < GT; ++t)
-        scores[int64_t(h0 + t) * s.total_kv + kv0 + r0 + lane] = acc[t] + 0.0f;
-    }
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -243,15 +263,20 @@ SelectPlan plan_select(const Shape& s) {
 template <int ES, int D>
 static hipError_t launch_score(const Shape& s, const void* k, const float* qsum, const int32_t* cu_kv,
                                const int32_t* cu_k, float* scores, hipStream_t st) {
-  dim3 grid((s.max_kv + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock, s.hkv, s.batch);
+  // up to four tiles per wave, as long as about four workgroups per compute unit remain
+  const int64_t wg_tiles = int64_t(s.total_kv) * s.hkv / kScoreRowsPerBlock;
+  int tpw = int(wg_tiles / 1024);
+  tpw = tpw < 1 ? 1 : (tpw > 4 ? 4 : tpw);
+  const int rows_per_block = kScoreRowsPerBlock * tpw;
+  dim3 grid(s.hkv, (s.max_kv + rows_per_block - 1) / rows_per_block, s.batch);
   dim3 block(kScoreWaves * 64);
   const char* kp = static_cast<const char*>(k);
   if (s.group % 4 == 0)
-    score_kernel<ES, D, 4><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, s);
+    score_kernel<ES, D, 4><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, tpw, s);
   else if (s.group % 2 == 0)
-    score_kernel<ES, D, 2><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, s);
+    score_kernel<ES, D, 2><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, tpw, s);
   else
-    score_kernel<ES, D, 1><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, s);
+    score_kernel<ES, D, 1><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, tpw, s);
   return hipGetLastError();
 }
 

@@ -54,7 +54,7 @@ def attend_status(b, idx=FAKE, cu_k=FAKE, total_k=100, max_k=50, mode=None, o=FA
 @pytest.mark.parametrize("field,value", [
     ("dtype", 7), ("batch", 0), ("n_q_heads", 0), ("n_kv_heads", 3), ("head_dim", 96), ("q", 0), ("k", None),
     ("cu_kv", 0), ("max_kv", 501), ("max_q", -1), ("q_stride_head", 64), ("kv_stride_tok", 257), ("v", 0x10008),
-    ("softmax_scale", float("inf")),
+    ("softmax_scale", float("inf")), ("softmax_scale", -0.5), ("softmax_scale", 0.0),
 ])
 def test_bad_batch_descriptor_is_rejected_everywhere(field, value):
     b = good_batch()
