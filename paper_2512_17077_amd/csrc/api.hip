@@ -102,14 +102,15 @@ AttendPlan plan_attend(const Shape& s, dllm_dtype dt, int32_t max_k) {
   p.chunk_rows = max_k > 0 ? max_k : 1;
   p.n_chunks = 1;
   if (dt == DLLM_BF16 && max_k > 0) {
-    // aim at about four workgroups per compute unit; chunks are multiples of the 128 rows four waves take
+    // Two workgroups of four waves fit a compute unit (512 slots on the chip).  With at least that many
+    // (sequence, head) pairs, chunks are as long as a wave's tile list allows (768 rows: six steps);
+    // with fewer pairs, kept lists are cut finer so the chip still fills.  Chunks are multiples of the
+    // 128 rows four waves take per step.
     const int64_t units = int64_t(s.batch) * s.hq;
-    int64_t want = 1024 / units;
+    int64_t want = 512 / units;
     if (want < 1) want = 1;
-    const int64_t most = (max_k + 127) / 128;
-    if (want > most) want = most;
-    int64_t rows = (max_k + want - 1) / want;
-    rows = (rows + 127) / 128 * 128;
+    int64_t rows = ((max_k + want - 1) / want + 127) / 128 * 128;
+    if (rows > 2048) rows = 2048;
     p.chunk_rows = int32_t(rows);
     p.n_chunks = int32_t((max_k + rows - 1) / rows);
   }

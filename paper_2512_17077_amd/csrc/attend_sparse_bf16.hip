@@ -19,6 +19,64 @@ namespace dllm {
 constexpr int kTile = 32;        // kept rows per wave tile
 constexpr int kWaves = 4;
 constexpr float kLazyStepS = 8.0f;
+constexpr int kMaxTilesPerWave = 16;  // chunk_rows <= kMaxTilesPerWave * kWaves * kTile
+constexpr int kRankBatch = 64;        // batches up to this size are walked longest kept list first
+
+// A (sequence, head) with kb kept rows is cut into n = ceil(kb / chunk_rows) chunks of equal size
+// (rounded up to the 128 rows four waves take per step), so no chunk is a short leftover.
+struct ChunkGeom {
+  int n, rows;
+};
+__device__ __forceinline__ ChunkGeom chunk_geom(int kb, int chunk_rows) {
+  ChunkGeom g;
+  g.n = (kb + chunk_rows - 1) / chunk_rows;
+  g.rows = g.n <= 1 ? chunk_rows : ((kb + g.n - 1) / g.n + 127) / 128 * 128;
+  return g;
+}
+
+// Per-sequence offsets a workgroup needs, fetched for the whole (small) batch in one round of
+// loads: lane i holds sequence i's entries, and the chosen sequence's are read back by lane index.
+struct SeqInfo {
+  int b, ko0, kb, q0, nq, kv0;
+};
+
+// Sequence handled by grid slot z.  With `ranked` set (small batches whose workgroups do not all fit
+// on the chip at once) sequences are taken in descending order of kept rows (ties: lower sequence
+// first), so the longest lists start first and the short ones fill the compute units that free up;
+// every workgroup derives the same order from cu_k.
+__device__ __forceinline__ SeqInfo sequence_of_slot(const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv,
+                                                    const int32_t* __restrict__ cu_k, int batch, int z, int lane,
+                                                    bool ranked) {
+  SeqInfo si;
+  if (batch > kRankBatch) {
+    si.b = z;
+    si.ko0 = cu_k[z]; si.kb = cu_k[z + 1] - si.ko0;
+    si.q0 = cu_q[z]; si.nq = cu_q[z + 1] - si.q0;
+    si.kv0 = cu_kv[z];
+    return si;
+  }
+  const int i = lane < batch ? lane : batch - 1;
+  const int ko0 = cu_k[i], kb = cu_k[i + 1] - ko0;
+  const int q0 = cu_q[i], nq = cu_q[i + 1] - q0;
+  const int kv0 = cu_kv[i];
+  int b = z;
+  if (ranked) {
+    const int mine = lane < batch ? kb : -1;
+    int rank = 0;
+    for (int j = 0; j < batch; ++j) {
+      const int other = __builtin_amdgcn_readlane(mine, j);
+      rank += (other > mine) || (other == mine && j < lane);
+    }
+    b = __builtin_ctzll(__builtin_amdgcn_ballot_w64(lane < batch && rank == z));
+  }
+  si.b = b;
+  si.ko0 = __builtin_amdgcn_readlane(ko0, b);
+  si.kb = __builtin_amdgcn_readlane(kb, b);
+  si.q0 = __builtin_amdgcn_readlane(q0, b);
+  si.nq = __builtin_amdgcn_readlane(nq, b);
+  si.kv0 = __builtin_amdgcn_readlane(kv0, b);
+  return si;
+}
 
 template <int D>
 __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
@@ -26,7 +84,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cu_k, int32_t total_k, const uint8_t* __restrict__ seq_mode,
     uint16_t* __restrict__ o, float* __restrict__ po, float* __restrict__ pm, float* __restrict__ pl,
-    int32_t chunk_rows, Shape s) {
+    int32_t chunk_rows, int ranked, Shape s) {
   constexpr int CH = D / 8;             // 16-byte chunks per row
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = kTile * ROWB;
@@ -37,19 +95,23 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
   // per wave: K tile then V tile; reused as fp32 merge space afterwards
   __shared__ __attribute__((aligned(16))) char lds[kWaves][2 * TILEB];
   __shared__ float sm_m[kWaves][32], sm_l[kWaves][32];
+  __shared__ int sm_rows[kWaves][kMaxTilesPerWave * kTile];   // kept-row ids of each wave's tiles
 
-  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE) return;
-  const int ko0 = cu_k[b], kb = cu_k[b + 1] - ko0;
-  const int c0 = chunk * chunk_rows;
-  if (c0 >= kb && !(chunk == 0 && kb == 0)) return;
-  const int c1 = min(kb, c0 + chunk_rows);
-  const int nch_b = (kb + chunk_rows - 1) / chunk_rows;
-  const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
-  const int kv0 = cu_kv[b];
-  const int g = h / s.group;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int col = lane & 31, hf = lane >> 5;
+  const int chunk = blockIdx.x, h = blockIdx.y;
+  const SeqInfo si = sequence_of_slot(cu_q, cu_kv, cu_k, s.batch, blockIdx.z, lane, ranked != 0);
+  const int b = si.b;
+  if (seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE) return;
+  const int ko0 = si.ko0, kb = si.kb;
+  const ChunkGeom cg = chunk_geom(kb, chunk_rows);
+  const int c0 = chunk * cg.rows;
+  if (c0 >= kb && !(chunk == 0 && kb == 0)) return;
+  const int c1 = min(kb, c0 + cg.rows);
+  const int nch_b = cg.n;
+  const int q0 = si.q0, nq = si.nq;
+  const int kv0 = si.kv0;
+  const int g = h / s.group;
 
   if (kb == 0) {  // nothing kept: defined as zeros
     for (int e = threadIdx.x; e < nq * D; e += kWaves * 64)
@@ -98,35 +160,37 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
       for (int i = 0; i < 16; ++i) acc[db][i] = 0.0f;
 
     v4u kr[NLD], vr[NLD];
-    // my_row: this lane's kept-row id for tile row (lane & 31); rows past the end repeat a valid row
-    // and are masked out of the softmax below
-    auto fetch = [&](int my_row) {
+    // Kept-row ids of every tile this wave will walk go to LDS once (positions past the end repeat
+    // the last kept row; such rows are masked out of the softmax below).
+    int* my_rows = sm_rows[wave];
+#pragma unroll
+    for (int j = 0; j < kMaxTilesPerWave / 2; ++j) {
+      const int slot = j * 64 + lane;   // tile slot / 32, row slot % 32 of this wave
+      const int t = min(c0 + (wave + (slot >> 5) * kWaves) * kTile + (slot & 31), c1 - 1);
+      my_rows[slot] = rows[t];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    auto fetch = [&](int j) {   // gather the wave's j-th tile into registers
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int row = (i * 64 + lane) / CH;
-        const int64_t r = __shfl(my_row, row);
+        const int64_t r = my_rows[j * kTile + (i * 64 + lane) / CH];
         kr[i] = *reinterpret_cast<const v4u*>(kbase + r * pitch + coff);
         vr[i] = *reinterpret_cast<const v4u*>(vbase + r * pitch + coff);
       }
     };
-    auto row_of = [&](int tile) -> int {
-      const int t = min(c0 + tile * kTile + col, c1 - 1);
-      return tile < ntiles ? rows[t] : 0;
-    };
 
     int tile = wave;
-    int row_next = row_of(tile);
-    if (tile < ntiles) fetch(row_next);
-    row_next = row_of(tile + kWaves);
+    if (tile < ntiles) fetch(0);
 
-    for (; tile < ntiles; tile += kWaves) {
+    for (int j = 0; tile < ntiles; ++j, tile += kWaves) {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
         *reinterpret_cast<v4u*>(ktile + woff[i]) = kr[i];
         *reinterpret_cast<v4u*>(vtile + woff[i]) = vr[i];
       }
-      if (tile + kWaves < ntiles) fetch(row_next);
-      row_next = row_of(tile + 2 * kWaves);
+      if (tile + kWaves < ntiles) fetch(j + 1);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -253,7 +317,7 @@ __global__ __launch_bounds__(256) void attend_sparse_combine_kernel(
   const int h = blockIdx.x, b = blockIdx.y;
   if (seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE) return;
   const int kb = cu_k[b + 1] - cu_k[b];
-  const int nch = (kb + chunk_rows - 1) / chunk_rows;
+  const int nch = chunk_geom(kb, chunk_rows).n;
   if (nch <= 1) return;
   const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
   constexpr int EPT = D / 8;   // elements per thread
@@ -295,12 +359,14 @@ hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const 
                  *vh = static_cast<const uint16_t*>(v);
   uint16_t* oh = static_cast<uint16_t*>(o);
   dim3 grid(p.n_chunks, s.hq, s.batch);
+  // the start order only matters when the workgroups cannot all be resident at once (two per compute unit)
+  const int ranked = int64_t(p.n_chunks) * s.hq * s.batch > 512 ? 1 : 0;
   if (s.d == 128)
     attend_sparse_bf16_kernel<128><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
-                                                                seq_mode, oh, po, pm, pl, p.chunk_rows, s);
+                                                                seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
   else
     attend_sparse_bf16_kernel<64><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
-                                                               seq_mode, oh, po, pm, pl, p.chunk_rows, s);
+                                                               seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_chunks <= 1) return e;
   dim3 cgrid(s.hq, s.batch);
