@@ -26,13 +26,20 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 
-# HBM bytes per launch from rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, scaled by the same
-# counters over a plain copy of known size); see profiles/.  None where not collected.
+# HBM bytes per launch (reads + writes) from two rocprofv3 --pmc runs of this script (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what it reads for the --copy-probe launch of known size); the summary,
+# with the commands, is profiles/hbm_traffic_pmc.md.  They are properties of the workload shapes
+# above, not of the timing, so they are recorded here rather than re-measured on every run.
 TRAFFIC_BYTES = {
-    "attend_dense_bf16_kernel": None,
-    "attend_sparse_bf16_kernel": None,
-    "score_kernel": None,
+    "attend_dense_bf16_kernel": 536.97e6,    # Refresh c4: 402.8 MB read + 134.2 MB written
+    "attend_sparse_bf16_kernel": 205.82e6,   # Reuse c3: 196.9 MB read + 8.9 MB written
+    "score_kernel": 288.09e6,                # Reuse c3: 283.1 MB read + 5.0 MB written
 }
+
+# What plain kernels reach on this GPU (python -m paper_2512_17077_amd.ceilings; profiles/ceilings_microbench.md):
+# context for the fractions of the published peaks, never used as the roofline denominator.
+MEASURED_CEILINGS = {"hbm_stream_read_GBps": 5129.0, "hbm_row_gather_GBps": 4883.0,
+                     "mfma_bf16_sustained_TFLOPs": 2034.0, "shader_clock_under_mfma_MHz": 1993.0}
 
 
 def parse():
@@ -138,9 +145,10 @@ def main():
                   Timed("attend_mixed", lambda: d5.attend(workspace=ws5a))]
 
     if args.copy_probe:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        # one plain elementwise pass of known size: reads 1 GiB, writes 1 GiB (dst = src + 1 on int32)
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda:0")
         dst = torch.empty_like(src)
-        dst.copy_(src)
+        torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
         del src, dst
 
@@ -215,6 +223,7 @@ def main():
                                w3.attend_sparse_bytes()),
         "roofline_select": roof("hbm", select_gbps, HBM_PEAK_GBPS, "GB/s", "score_kernel", w3.select_bytes()),
         "peaks": {"hbm_GBps": HBM_PEAK_GBPS, "mfma_bf16_dense_TFLOPs": MFMA_BF16_PEAK_TFLOPS},
+        "measured_ceilings_context": MEASURED_CEILINGS,
         "paper_context": "dLLM-Serve reports end-to-end serving gains only (1.61-1.81x on RTX 4090, "
                          "1.60-1.74x on L40S); no kernel-level number exists for this path",
     }

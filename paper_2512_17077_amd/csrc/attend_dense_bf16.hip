@@ -46,12 +46,17 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
 
   // Workgroups are handed to the eight XCDs round-robin by launch order, and each XCD has its own
   // L2.  Renumber so that the query tiles of one (sequence, head), which all stream the same K/V,
-  // are launch-order neighbours modulo 8: they then share one L2 instead of fetching K/V eight times.
-  const int nx = gridDim.x, total = nx * gridDim.y * gridDim.z;
+  // land on one XCD (launch ids equal modulo 8) and share its L2 instead of fetching K/V eight
+  // times, while consecutive (sequence, head) pairs still go to different XCDs.
+  const int nx = gridDim.x, groups = gridDim.y * gridDim.z;
   const int n = blockIdx.x + nx * (blockIdx.y + gridDim.y * blockIdx.z);
-  const int per_xcd = total >> 3;
-  const int m = n < per_xcd * 8 ? (n & 7) * per_xcd + (n >> 3) : n;
-  const int qtile = m % nx, h = (m / nx) % gridDim.y, b = m / (nx * gridDim.y);
+  int qtile = blockIdx.x, gi = blockIdx.y + gridDim.y * blockIdx.z;
+  if ((groups & 7) == 0) {
+    const int j = n >> 3;   // position in this XCD's own launch sequence
+    qtile = j % nx;
+    gi = (j / nx) * 8 + (n & 7);
+  }
+  const int h = gi % gridDim.y, b = gi / gridDim.y;
   if (which == 1 && !(seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE)) return;
   const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
   const int qbase = qtile * QROWS;
