@@ -1,8 +1,18 @@
 // Refresh-phase attention (Section 2.3, Eq. 3): dense bidirectional softmax attention, bf16 inputs,
 // fp32 softmax state and accumulators, on the gfx950 matrix cores.  This path is a dense
 // contraction (4*Lq*Lkv*D flop per head against O(L*D) bytes), so it is bound by MFMA throughput,
-// with the softmax's exponentials on the vector ALUs as the co-bottleneck (about as many VALU
-// cycles as MFMA cycles per step), so the two have to overlap.
+// with the softmax's exponentials on the vector ALUs as the co-bottleneck: one v_exp_f32 per score
+// costs a quarter-rate issue slot, which alone is half of the MFMA time of a step.  Everything else
+// on the vector ALUs is therefore kept to a minimum:
+//   - Q is scaled by softmax_scale * log2(e) once, when it is loaded (rounded to bf16 again), and the
+//     score MFMA chain starts from the accumulator value -m (the running maximum) instead of 0, so
+//     the scores leave the matrix core ready for exp2: no multiply-add per score;
+//   - the running maximum is raised lazily (only when a score exceeds it by more than 2^8, so
+//     probabilities may exceed 1 until then) and that rare rescale sits behind a uniform branch;
+//   - the key loop is unrolled over one turn of the LDS ring (six 32-key steps), so every LDS
+//     address is a register fixed before the loop plus an immediate offset;
+//   - the row sums come from the packed bf16 probabilities (two per v_dot2c), the same values the
+//     P*V product uses.
 //
 // A workgroup owns WAVES * NQB * 32 query rows of one (sequence, head); each wave keeps its queries
 // as B operands in registers for the whole pass.  K/V tiles of 64 keys are loaded by all threads
@@ -11,12 +21,11 @@
 //
 // Each wave walks the keys in steps of 32 with a software pipeline, so that every stretch of MFMAs
 // has independent vector work issued between them:
-//   stage 1   S^T(i+1) = K * Q^T          (MFMA, A by ds_read_b128)  ||  exp2 of step i, keys 0..15
+//   stage 1   S^T(i+1) = K * Q^T - m      (MFMA, A by ds_read_b128)  ||  exp2 of step i, keys 0..15
 //   stage 2   O^T += V^T P^T, keys 0..15  (MFMA, A by ds_read_b64_tr) ||  exp2 of step i, keys 16..31
 //   stage 3   O^T += V^T P^T, keys 16..31 (MFMA)                      ||  row maxima of step i+1
-// The running maximum is updated lazily: the accumulators are rescaled only when some query's
-// maximum grew by more than 2^8 (probabilities may exceed 1 until then), and that rare rescale runs
-// outside the hot loop, which then resumes at the next step.
+#include <type_traits>
+
 #include "attn_tile.h"
 
 namespace dllm {
@@ -35,14 +44,16 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   constexpr int CH = D / 8;
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = kDenseK * ROWB;
+  constexpr int VBASE = kDenseRing * TILEB;      // V tiles follow the K tiles
   constexpr int NTHREADS = WAVES * 64;
   constexpr int QROWS = WAVES * 32 * NQB;
   constexpr int NLD = kDenseK * CH / NTHREADS;   // 16-byte loads per thread, tile and tensor
   constexpr int NT = D / 16;
   constexpr int NDB = D / 32;
+  constexpr int ROUND = 2 * kDenseRing;          // steps in one turn of the ring
   static_assert(NLD >= 1, "too many threads for one tile");
 
-  __shared__ __attribute__((aligned(16))) char smem[kDenseRing][2][TILEB];   // [ring slot][K, V]
+  __shared__ __attribute__((aligned(16))) char smem[2 * kDenseRing * TILEB];   // K ring, then V ring
 
   // Workgroups are handed to the eight XCDs round-robin by launch order, and each XCD has its own
   // L2.  Renumber so that the query tiles of one (sequence, head), which all stream the same K/V,
@@ -74,7 +85,8 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     return;
   }
 
-  // Q^T operands: lane (col = query, hf) holds Q[query][16t + 8hf .. +8) for every step t
+  // Q^T operands: lane (col = query, hf) holds zscale * Q[query][16t + 8hf .. +8) for every step t
+  const float zscale = s.scale * kLog2e;   // > 0
   v4u qreg[NQB][NT];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
@@ -82,19 +94,32 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     const uint16_t* qp = q + int64_t(q0 + qi) * s.q_tok + int64_t(h) * s.q_head;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      qreg[qb][t] = v4u{0u, 0u, 0u, 0u};
-      if (qi < nq) qreg[qb][t] = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
+      v4u x = v4u{0u, 0u, 0u, 0u};
+      if (qi < nq) x = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
+      qreg[qb][t] = v4u{cvt_pk_bf16(bf16_lo(x.x) * zscale, bf16_hi(x.x) * zscale),
+                        cvt_pk_bf16(bf16_lo(x.y) * zscale, bf16_hi(x.y) * zscale),
+                        cvt_pk_bf16(bf16_lo(x.z) * zscale, bf16_hi(x.z) * zscale),
+                        cvt_pk_bf16(bf16_lo(x.w) * zscale, bf16_hi(x.w) * zscale)};
     }
   }
   const char* kbase = reinterpret_cast<const char*>(k + int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head);
   const char* vbase = reinterpret_cast<const char*>(v + int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head);
   const int64_t pitch = s.kv_tok * 2;
-  const float zscale = s.scale * kLog2e;   // > 0
 
-  KAddr<D> ka;
-  ka.init(lane);
-  VtAddr<D> vt;
-  vt.init(lane);
+  // LDS addresses, fixed for the whole pass; ring slot, 32-key half and 16-key quarter are immediates
+  int ka[NT], va[2][NDB];
+  {
+    KAddr<D> kaddr;
+    kaddr.init(lane);
+    VtAddr<D> vaddr;
+    vaddr.init(lane);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) ka[t] = kaddr.off(t);
+#pragma unroll
+    for (int rd = 0; rd < 2; ++rd)
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) va[rd][db] = VBASE + vaddr.off(rd, db);
+  }
   int woff[NLD];   // where this thread's loaded chunks go inside a tile
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
@@ -102,13 +127,16 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     woff[i] = tile_off<D>(f / CH, f % CH);
   }
 
-  float m_used[NQB], lsum[NQB], tmax[NQB];
+  // running maximum m (base-2 logits), kept negated in all 16 registers of an accumulator so that
+  // it can seed the score MFMA chain; row sum; output accumulators
+  f32x16 negm[NQB];
+  float lsum[NQB];
   f32x16 acc[NQB][NDB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    m_used[qb] = -INFINITY;
     lsum[qb] = 0.0f;
-    tmax[qb] = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) negm[qb][i] = 0.0f;
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -132,20 +160,22 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   auto stage = [&](int slot) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      *reinterpret_cast<v4u*>(&smem[slot][0][woff[i]]) = kr[i];
-      *reinterpret_cast<v4u*>(&smem[slot][1][woff[i]]) = vr[i];
+      *reinterpret_cast<v4u*>(smem + slot * TILEB + woff[i]) = kr[i];
+      *reinterpret_cast<v4u*>(smem + VBASE + slot * TILEB + woff[i]) = vr[i];
     }
   };
-  // scores of one 32-key step for this wave's queries: rows = keys, columns = queries
-  auto scores = [&](f32x16 (&st)[NQB], int step) {
-    const char* kt = smem[(step >> 1) % kDenseRing][0] + (step & 1) * 32 * ROWB;
+  // scores of the 32-key step at byte offset `koff` of the K ring, relative to the running maxima:
+  // rows = keys, columns = this wave's queries
+  auto scores = [&](f32x16 (&st)[NQB], int koff) {
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) st[qb][i] = 0.0f;
+    for (int qb = 0; qb < NQB; ++qb) st[qb] = negm[qb];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const v4u a = *reinterpret_cast<const v4u*>(kt + ka.off(t));
+#ifdef DLLM_ABL_NOLDSREAD
+      const v4u a = qreg[0][(t + 1) % NT];
+#else
+      const v4u a = *reinterpret_cast<const v4u*>(smem + ka[t] + koff);
+#endif
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) st[qb] = mfma_bf16(a, qreg[qb][t], st[qb]);
     }
@@ -160,41 +190,60 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
         if (key >= nvalid) st[qb][i] = -INFINITY;
       }
   };
-  // row maxima of a step; true if some query of this wave needs its running maximum raised
-  auto maxima = [&](const f32x16 (&st)[NQB]) -> bool {
-    bool gr = false;
+  // largest score of a step per lane (a query's scores sit in the lane pair l, l ^ 32)
+  auto lane_max = [&](const f32x16& st) -> float {
+    float mx = fmaxf(st[0], st[1]);
+#pragma unroll
+    for (int i = 2; i < 16; i += 2) mx = fmaxf(fmaxf(mx, st[i]), st[i + 1]);
+    return mx;
+  };
+  // Raise the running maxima by delta >= 0 per query and rescale what was accumulated under the old
+  // ones, including the scores `st` already computed relative to them.
+  auto raise = [&](f32x16 (&st)[NQB], const float (&delta)[NQB]) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      float mx = fmaxf(st[qb][0], st[qb][1]);
+      const float alpha = __builtin_amdgcn_exp2f(-delta[qb]);
+      lsum[qb] *= alpha;
 #pragma unroll
-      for (int i = 2; i < 16; i += 2) mx = fmaxf(fmaxf(mx, st[qb][i]), st[qb][i + 1]);
-      tmax[qb] = max_across_halves(mx) * zscale;
-      gr = gr || (tmax[qb] > m_used[qb] + kLazyStep);
+      for (int i = 0; i < 16; ++i) {
+        negm[qb][i] -= delta[qb];
+        st[qb][i] -= delta[qb];
+      }
+#pragma unroll
+      for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[qb][db][e] *= alpha;
     }
-    return __builtin_amdgcn_ballot_w64(gr) != 0;
   };
   // probabilities of keys 16u .. 16u+15 of a step, packed as the B operand of the P*V MFMAs
   auto probs = [&](const f32x16 (&st)[NQB], int u, v4u (&pb)[NQB]) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      const float neg_m = -m_used[qb];
       uint32_t w[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qb][8 * u + 2 * j], zscale, neg_m));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[qb][8 * u + 2 * j + 1], zscale, neg_m));
+#ifdef DLLM_ABL_NOEXP
+        const float p0 = st[qb][8 * u + 2 * j], p1 = st[qb][8 * u + 2 * j + 1];
+#else
+        const float p0 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j]);
+        const float p1 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j + 1]);
+#endif
         w[j] = cvt_pk_bf16(p0, p1);
         lsum[qb] = add_pair_bf16(w[j], lsum[qb]);
       }
       pb[qb] = v4u{w[0], w[1], w[2], w[3]};
     }
   };
-  auto accumulate = [&](const char* vtile, int u, const v4u (&pb)[NQB]) {
+  auto accumulate = [&](int voff, const v4u (&pb)[NQB]) {
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
-      const v2u lo = lds_read_tr16(vtile + vt.off(0, db) + 16 * u * ROWB);
-      const v2u hi = lds_read_tr16(vtile + vt.off(1, db) + 16 * u * ROWB);
+#ifdef DLLM_ABL_NOLDSREAD
+      const v4u a = qreg[0][db];
+#else
+      const v2u lo = lds_read_tr16(smem + va[0][db] + voff);
+      const v2u hi = lds_read_tr16(smem + va[1][db] + voff);
       const v4u a = v4u{lo.x, lo.y, hi.x, hi.y};
+#endif
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) acc[qb][db] = mfma_bf16(a, pb[qb], acc[qb][db]);
     }
@@ -210,56 +259,70 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   if (ntiles > 2) fetch(2);
   __syncthreads();
 
-  f32x16 st_cur[NQB];
-  scores(st_cur, 0);
-  if (nsteps == 1 && rem) mask_tail(st_cur, rem);
-  bool grow = maxima(st_cur);   // always true here: the running maxima start at -inf
+  f32x16 st_a[NQB], st_b[NQB];
+  scores(st_a, 0);
+  if (nsteps == 1 && rem) mask_tail(st_a, rem);
+  {   // the first step sets the maxima outright (they may be negative)
+    float delta[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) delta[qb] = max_across_halves(lane_max(st_a[qb]));
+    raise(st_a, delta);
+  }
+
+  // One 32-key step.  R (0..5) is its position in the turn of the ring, which fixes every LDS offset:
+  // the step reads V of ring slot R/2, half R%2, and computes the scores of the step after it.
   int i = 0;
+  auto step = [&](auto rc, f32x16 (&cur)[NQB], f32x16 (&nxt)[NQB]) {
+    constexpr int R = decltype(rc)::value;
+    constexpr int slot = R / 2, kb = R % 2;
+    constexpr int RN = (R + 1) % ROUND;
+    const int tile = i >> 1;
+    if (kb == 0) {   // tile boundary: everyone is done with tile-1; tile+1 (staged a tile ago) becomes visible
+      __syncthreads();
+#ifndef DLLM_ABL_NOSTAGE
+      if (tile + 2 < ntiles) stage((slot + 2) % kDenseRing);
+      if (tile + 3 < ntiles) fetch(tile + 3);
+#endif
+    }
+    constexpr int voff = slot * TILEB + kb * 32 * ROWB;
+    v4u pb0[NQB], pb1[NQB];
+    // stage 1 (past the last step the scores are computed from stale LDS and never used)
+    scores(nxt, (RN / 2) * TILEB + (RN % 2) * 32 * ROWB);
+    probs(cur, 0, pb0);
+    // stage 2
+    accumulate(voff, pb0);
+    probs(cur, 1, pb1);
+    // stage 3
+    if (rem && i + 2 == nsteps) mask_tail(nxt, rem);
+    accumulate(voff + 16 * ROWB, pb1);
+    bool grow = false;
+    float mx[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      mx[qb] = lane_max(nxt[qb]);
+      grow = grow || (mx[qb] > kLazyStep);
+    }
+    ++i;
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0 && i < nsteps, 0)) {
+      float delta[NQB];
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) delta[qb] = fmaxf(max_across_halves(mx[qb]), 0.0f);
+      raise(nxt, delta);
+    }
+  };
   for (;;) {
-    if (grow) {   // rare after the first step: raise the running maxima, rescale what was accumulated
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        const float m_new = fmaxf(m_used[qb], tmax[qb]);
-        const float alpha = __builtin_amdgcn_exp2f(m_used[qb] - m_new);   // exp2(-inf) = 0 the first time
-        m_used[qb] = m_new;
-        lsum[qb] *= alpha;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc[qb][db][e] *= alpha;
-      }
-      grow = false;
-    }
-    while (i < nsteps) {
-      const int tile = i >> 1, kb = i & 1;
-      if (kb == 0) {   // tile boundary: everyone is done with tile-1; tile+1 (staged a tile ago) becomes visible
-        __syncthreads();
-        if (tile + 2 < ntiles) stage((tile + 2) % kDenseRing);
-        if (tile + 3 < ntiles) fetch(tile + 3);
-      }
-      const int inext = min(i + 1, nsteps - 1);   // past the end: a valid step again, result unused
-      const char* vtile = smem[tile % kDenseRing][1] + kb * 32 * ROWB;
-      f32x16 st_next[NQB];
-      v4u pb0[NQB], pb1[NQB];
-      // stage 1
-      scores(st_next, inext);
-      probs(st_cur, 0, pb0);
-      // stage 2
-      accumulate(vtile, 0, pb0);
-      probs(st_cur, 1, pb1);
-      // stage 3
-      if (rem && i + 2 == nsteps) mask_tail(st_next, rem);
-      accumulate(vtile, 1, pb1);
-      const bool gr = maxima(st_next);
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) st_cur[qb] = st_next[qb];
-      ++i;
-      if (__builtin_expect(gr && i < nsteps, 0)) {
-        grow = true;
-        break;
-      }
-    }
-    if (!grow) break;
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 0>{}, st_a, st_b);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 1>{}, st_b, st_a);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 2>{}, st_a, st_b);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 3>{}, st_b, st_a);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 4>{}, st_a, st_b);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 5>{}, st_b, st_a);
   }
 
 #pragma unroll
@@ -283,9 +346,15 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   }
 }
 
-// Two waves per SIMD (eight per workgroup, one 32-query block each) measured fastest on MI355X: the
-// second wave fills the issue slots the first leaves while it waits on LDS or on a dependent MFMA.
-constexpr int kDenseQB = 1, kDenseWaves = 8;
+// Two waves per SIMD (eight per workgroup, one 32-query block each): the second wave fills the
+// issue slots the first leaves while it waits on LDS or on a dependent MFMA.
+#ifndef DLLM_DENSE_QB
+#define DLLM_DENSE_QB 1
+#endif
+#ifndef DLLM_DENSE_WAVES
+#define DLLM_DENSE_WAVES 8
+#endif
+constexpr int kDenseQB = DLLM_DENSE_QB, kDenseWaves = DLLM_DENSE_WAVES;
 
 hipError_t launch_attend_dense_bf16(const Shape& s, const void* q, const void* k, const void* v,
                                     const int32_t* cu_q, const int32_t* cu_kv, const uint8_t* seq_mode, int which,

@@ -176,8 +176,8 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
         const int64_t r = my_rows[j * kTile + (i * 64 + lane) / CH];
-        kr[i] = *reinterpret_cast<const v4u*>(kbase + r * pitch + coff);
-        vr[i] = *reinterpret_cast<const v4u*>(vbase + r * pitch + coff);
+        kr[i] = load_once(kbase + r * pitch + coff);
+        vr[i] = load_once(vbase + r * pitch + coff);
       }
     };
 

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int row = min(r0 + (i * 64 + lane) / CH, L - 1);
-      regs[i] = *reinterpret_cast<const v4u*>(base + row * row_pitch);
+      regs[i] = load_once(base + row * row_pitch);
     }
   };
   fetch(first);
@@ -266,7 +266,10 @@ static hipError_t launch_score(const Shape& s, const void* k, const float* qsum,
   // up to four tiles per wave, as long as about four workgroups per compute unit remain
   const int64_t wg_tiles = int64_t(s.total_kv) * s.hkv / kScoreRowsPerBlock;
   int tpw = int(wg_tiles / 1024);
-  tpw = tpw < 1 ? 1 : (tpw > 4 ? 4 : tpw);
+#ifndef DLLM_SCORE_TPW_MAX
+#define DLLM_SCORE_TPW_MAX 4
+#endif
+  tpw = tpw < 1 ? 1 : (tpw > DLLM_SCORE_TPW_MAX ? DLLM_SCORE_TPW_MAX : tpw);
   const int rows_per_block = kScoreRowsPerBlock * tpw;
   dim3 grid(s.hkv, (s.max_kv + rows_per_block - 1) / rows_per_block, s.batch);
   dim3 block(kScoreWaves * 64);
