@@ -1,26 +1,28 @@
 // Refresh-phase attention (Section 2.3, Eq. 3): dense bidirectional softmax attention, bf16 inputs,
 // fp32 softmax state and accumulators, on the gfx950 matrix cores.  This path is a dense
-// contraction (4*Lq*Lkv*D flop per head against O(L*D) bytes), so it is bound by MFMA throughput,
-// with the softmax's exponentials on the vector ALUs as the co-bottleneck: one v_exp_f32 per score
-// costs a quarter-rate issue slot, which alone is half of the MFMA time of a step.  Everything else
-// on the vector ALUs is therefore kept to a minimum:
+// contraction (4*Lq*Lkv*D flop per head against O(L*D) bytes), so it is bound by MFMA throughput.
+// Measured on MI355X, MFMA co-issues with v_exp_f32 and plain vector work almost for free; what costs
+// time is everything that makes waves wait: the start and end of a workgroup, workgroup barriers,
+// staging K/V through registers, and LDS read latency.  Hence:
+//   - a workgroup is four waves (128 query rows of one (sequence, head)) and uses 80 KB of LDS, so two
+//     workgroups share a compute unit and run out of phase: one's prologue, epilogue and barrier waits
+//     are covered by the other's matrix work;
+//   - K/V tiles of 64 keys go from global memory straight into LDS (global_load_lds, 16 bytes per
+//     lane), issued right after the tile barrier and due one tile later: no staging registers, no LDS
+//     writes, and the prologue's loads (Q, two K tiles, one V tile) are all in flight at once.  LDS
+//     tiles are XOR-swizzled by row; since the LDS side of such a load is lane-contiguous, the swizzle
+//     is applied to the global chunk each lane fetches (a permutation inside one 2*D-byte row);
+//   - K lives in a ring of three tiles (its scores are computed one step ahead), V in a ring of two;
 //   - Q is scaled by softmax_scale * log2(e) once, when it is loaded (rounded to bf16 again), and the
 //     score MFMA chain starts from the accumulator value -m (the running maximum) instead of 0, so
-//     the scores leave the matrix core ready for exp2: no multiply-add per score;
+//     the scores leave the matrix core ready for exp2;
 //   - the running maximum is raised lazily (only when a score exceeds it by more than 2^8, so
-//     probabilities may exceed 1 until then) and that rare rescale sits behind a uniform branch;
-//   - the key loop is unrolled over one turn of the LDS ring (six 32-key steps), so every LDS
-//     address is a register fixed before the loop plus an immediate offset;
-//   - the row sums come from the packed bf16 probabilities (two per v_dot2c), the same values the
-//     P*V product uses.
+//     probabilities may exceed 1 until then) behind a uniform branch;
+//   - the key loop is unrolled over one common turn of both rings (twelve 32-key steps), so every LDS
+//     address is a register fixed before the loop plus an immediate offset.
 //
-// A workgroup owns WAVES * NQB * 32 query rows of one (sequence, head); each wave keeps its queries
-// as B operands in registers for the whole pass.  K/V tiles of 64 keys are loaded by all threads
-// (16-byte loads, whole rows per 16 lanes), prefetched into registers three tiles ahead of their use
-// and staged in a three-deep ring of XOR-swizzled LDS tiles: one barrier per tile.
-//
-// Each wave walks the keys in steps of 32 with a software pipeline, so that every stretch of MFMAs
-// has independent vector work issued between them:
+// Each wave keeps its 32 queries as MFMA B operands in registers for the whole pass and walks the keys
+// in steps of 32 with a software pipeline:
 //   stage 1   S^T(i+1) = K * Q^T - m      (MFMA, A by ds_read_b128)  ||  exp2 of step i, keys 0..15
 //   stage 2   O^T += V^T P^T, keys 0..15  (MFMA, A by ds_read_b64_tr) ||  exp2 of step i, keys 16..31
 //   stage 3   O^T += V^T P^T, keys 16..31 (MFMA)                      ||  row maxima of step i+1
@@ -31,7 +33,8 @@
 namespace dllm {
 
 constexpr int kDenseK = 64;          // keys per LDS tile
-constexpr int kDenseRing = 3;        // LDS tiles in flight
+constexpr int kDenseRingK = 3;       // K tiles resident in LDS
+constexpr int kDenseRingV = 2;       // V tiles resident in LDS
 constexpr float kLazyStep = 8.0f;    // log2 of the growth that forces a rescale
 
 // NQB: 32-query blocks per wave; WAVES: waves per workgroup
@@ -44,16 +47,16 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   constexpr int CH = D / 8;
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = kDenseK * ROWB;
-  constexpr int VBASE = kDenseRing * TILEB;      // V tiles follow the K tiles
+  constexpr int VBASE = kDenseRingK * TILEB;     // V tiles follow the K tiles
   constexpr int NTHREADS = WAVES * 64;
   constexpr int QROWS = WAVES * 32 * NQB;
-  constexpr int NLD = kDenseK * CH / NTHREADS;   // 16-byte loads per thread, tile and tensor
+  constexpr int NLD = kDenseK * CH / NTHREADS;   // 16-byte loads per lane, tile and tensor
   constexpr int NT = D / 16;
   constexpr int NDB = D / 32;
-  constexpr int ROUND = 2 * kDenseRing;          // steps in one turn of the ring
-  static_assert(NLD >= 1, "too many threads for one tile");
+  constexpr int ROUND = 2 * kDenseRingK * kDenseRingV;   // steps in one common turn of both rings
+  static_assert(NLD >= 1 && kDenseK * CH % NTHREADS == 0, "tile does not split evenly over the threads");
 
-  __shared__ __attribute__((aligned(16))) char smem[2 * kDenseRing * TILEB];   // K ring, then V ring
+  __shared__ __attribute__((aligned(16))) char smem[(kDenseRingK + kDenseRingV) * TILEB];   // K ring, V ring
 
   // Workgroups are handed to the eight XCDs round-robin by launch order, and each XCD has its own
   // L2.  Renumber so that the query tiles of one (sequence, head), which all stream the same K/V,
@@ -120,12 +123,26 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
 #pragma unroll
       for (int db = 0; db < NDB; ++db) va[rd][db] = VBASE + vaddr.off(rd, db);
   }
-  int woff[NLD];   // where this thread's loaded chunks go inside a tile
+  // Global side of the tile loads: this lane's chunk f = i * NTHREADS + tid of a tile lands at LDS
+  // byte 16 * f, i.e. row f / CH, chunk slot f % CH, and must hold chunk (slot ^ swizzle(row)) of
+  // that row.  Rows past the end of the sequence re-read its last row (their keys are masked).
+  int ld_row[NLD], ld_col[NLD];
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
-    const int f = i * NTHREADS + tid;
-    woff[i] = tile_off<D>(f / CH, f % CH);
+    const int f = i * NTHREADS + tid, row = f / CH;
+    ld_row[i] = row;
+    ld_col[i] = ((f % CH) ^ tile_swz<D>(row)) << 4;
   }
+  // this wave's slice of each load round, as an LDS byte address
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 64 * 16);
+  auto load_tile = [&](const char* base, int tile, int lds_off) {
+    const int t0 = tile * kDenseK;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int row = min(t0 + ld_row[i], L - 1);
+      load16_to_lds(base + row * pitch + ld_col[i], wave_lds + lds_off + i * NTHREADS * 16);
+    }
+  };
 
   // running maximum m (base-2 logits), kept negated in all 16 registers of an accumulator so that
   // it can seed the score MFMA chain; row sum; output accumulators
@@ -143,42 +160,18 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       for (int i = 0; i < 16; ++i) acc[qb][db][i] = 0.0f;
   }
 
-  v4u kr[NLD], vr[NLD];
-  auto fetch = [&](int tile) {   // rows past the end of the sequence are zero-filled
-    const int t0 = tile * kDenseK;
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int f = i * NTHREADS + tid, row = f / CH, c = f % CH;
-      kr[i] = v4u{0u, 0u, 0u, 0u};
-      vr[i] = v4u{0u, 0u, 0u, 0u};
-      if (t0 + row < L) {
-        kr[i] = *reinterpret_cast<const v4u*>(kbase + (t0 + row) * pitch + c * 16);
-        vr[i] = *reinterpret_cast<const v4u*>(vbase + (t0 + row) * pitch + c * 16);
-      }
-    }
-  };
-  auto stage = [&](int slot) {
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      *reinterpret_cast<v4u*>(smem + slot * TILEB + woff[i]) = kr[i];
-      *reinterpret_cast<v4u*>(smem + VBASE + slot * TILEB + woff[i]) = vr[i];
-    }
-  };
   // scores of the 32-key step at byte offset `koff` of the K ring, relative to the running maxima:
   // rows = keys, columns = this wave's queries
   auto scores = [&](f32x16 (&st)[NQB], int koff) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) st[qb] = negm[qb];
+    v4u a[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-#ifdef DLLM_ABL_NOLDSREAD
-      const v4u a = qreg[0][(t + 1) % NT];
-#else
-      const v4u a = *reinterpret_cast<const v4u*>(smem + ka[t] + koff);
-#endif
+    for (int t = 0; t < NT; ++t) a[t] = *reinterpret_cast<const v4u*>(smem + ka[t] + koff);
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) st[qb] = mfma_bf16(a, qreg[qb][t], st[qb]);
-    }
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) st[qb] = mfma_bf16(a[t], qreg[qb][t], st[qb]);
   };
   auto mask_tail = [&](f32x16 (&st)[NQB], int nvalid) {   // keys past the end get no weight
     asm volatile("" ::: "memory");   // keep the caller's test a real (uniform) branch
@@ -222,12 +215,8 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       uint32_t w[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-#ifdef DLLM_ABL_NOEXP
-        const float p0 = st[qb][8 * u + 2 * j], p1 = st[qb][8 * u + 2 * j + 1];
-#else
         const float p0 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j]);
         const float p1 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j + 1]);
-#endif
         w[j] = cvt_pk_bf16(p0, p1);
         lsum[qb] = add_pair_bf16(w[j], lsum[qb]);
       }
@@ -235,28 +224,27 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     }
   };
   auto accumulate = [&](int voff, const v4u (&pb)[NQB]) {
+    v4u a[NDB];
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
-#ifdef DLLM_ABL_NOLDSREAD
-      const v4u a = qreg[0][db];
-#else
       const v2u lo = lds_read_tr16(smem + va[0][db] + voff);
       const v2u hi = lds_read_tr16(smem + va[1][db] + voff);
-      const v4u a = v4u{lo.x, lo.y, hi.x, hi.y};
-#endif
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) acc[qb][db] = mfma_bf16(a, pb[qb], acc[qb][db]);
+      a[db] = v4u{lo.x, lo.y, hi.x, hi.y};
     }
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) acc[qb][db] = mfma_bf16(a[db], pb[qb], acc[qb][db]);
   };
 
   const int rem = L % 32;
   const int nsteps = L / 32 + (rem ? 1 : 0);
   const int ntiles = (L + kDenseK - 1) / kDenseK;
 
-  fetch(0);
-  stage(0);
-  if (ntiles > 1) { fetch(1); stage(1); }
-  if (ntiles > 2) fetch(2);
+  load_tile(kbase, 0, 0);
+  load_tile(vbase, 0, VBASE);
+  if (ntiles > 1) load_tile(kbase, 1, TILEB);
+  wait_tile_loads();
   __syncthreads();
 
   f32x16 st_a[NQB], st_b[NQB];
@@ -269,31 +257,31 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     raise(st_a, delta);
   }
 
-  // One 32-key step.  R (0..5) is its position in the turn of the ring, which fixes every LDS offset:
-  // the step reads V of ring slot R/2, half R%2, and computes the scores of the step after it.
+  // One 32-key step.  R is its position in the common turn of the rings, which fixes every LDS
+  // offset: the step reads V tile (R/2) % 2, half R%2, and computes the scores of the step after it.
   int i = 0;
   auto step = [&](auto rc, f32x16 (&cur)[NQB], f32x16 (&nxt)[NQB]) {
     constexpr int R = decltype(rc)::value;
-    constexpr int slot = R / 2, kb = R % 2;
+    constexpr int T = R / 2, kb = R % 2;   // tile index modulo the turn
     constexpr int RN = (R + 1) % ROUND;
     const int tile = i >> 1;
-    if (kb == 0) {   // tile boundary: everyone is done with tile-1; tile+1 (staged a tile ago) becomes visible
+    if (kb == 0) {
+      // Tile boundary: everyone is done with tile-1, and the loads issued a tile ago (K of tile+1,
+      // V of this tile) have landed.  The slots of tile-1 take K of tile+2 and V of tile+1.
+      wait_tile_loads();
       __syncthreads();
-#ifndef DLLM_ABL_NOSTAGE
-      if (tile + 2 < ntiles) stage((slot + 2) % kDenseRing);
-      if (tile + 3 < ntiles) fetch(tile + 3);
-#endif
+      if (tile + 2 < ntiles) load_tile(kbase, tile + 2, ((T + 2) % kDenseRingK) * TILEB);
+      if (tile + 1 < ntiles) load_tile(vbase, tile + 1, VBASE + ((T + 1) % kDenseRingV) * TILEB);
     }
-    constexpr int voff = slot * TILEB + kb * 32 * ROWB;
+    constexpr int voff = (T % kDenseRingV) * TILEB + kb * 32 * ROWB;
     v4u pb0[NQB], pb1[NQB];
     // stage 1 (past the last step the scores are computed from stale LDS and never used)
-    scores(nxt, (RN / 2) * TILEB + (RN % 2) * 32 * ROWB);
+    scores(nxt, ((RN / 2) % kDenseRingK) * TILEB + (RN % 2) * 32 * ROWB);
     probs(cur, 0, pb0);
     // stage 2
     accumulate(voff, pb0);
     probs(cur, 1, pb1);
     // stage 3
-    if (rem && i + 2 == nsteps) mask_tail(nxt, rem);
     accumulate(voff + 16 * ROWB, pb1);
     bool grow = false;
     float mx[NQB];
@@ -303,7 +291,15 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       grow = grow || (mx[qb] > kLazyStep);
     }
     ++i;
-    if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0 && i < nsteps, 0)) {
+    // Rare path, one uniform branch: the next step is the ragged last one (mask the keys past the end,
+    // which were scored from a repeated row), or some score outgrew its running maximum.
+    const bool ragged = rem != 0 && i + 1 == nsteps;
+    if (__builtin_expect((__builtin_amdgcn_ballot_w64(grow) != 0 || ragged) && i < nsteps, 0)) {
+      if (ragged) {
+        mask_tail(nxt, rem);
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) mx[qb] = lane_max(nxt[qb]);
+      }
       float delta[NQB];
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) delta[qb] = fmaxf(max_across_halves(mx[qb]), 0.0f);
@@ -323,6 +319,18 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     step(std::integral_constant<int, 4>{}, st_a, st_b);
     if (i >= nsteps) break;
     step(std::integral_constant<int, 5>{}, st_b, st_a);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 6>{}, st_a, st_b);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 7>{}, st_b, st_a);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 8>{}, st_a, st_b);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 9>{}, st_b, st_a);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 10>{}, st_a, st_b);
+    if (i >= nsteps) break;
+    step(std::integral_constant<int, 11>{}, st_b, st_a);
   }
 
 #pragma unroll
@@ -346,13 +354,12 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   }
 }
 
-// Two waves per SIMD (eight per workgroup, one 32-query block each): the second wave fills the
-// issue slots the first leaves while it waits on LDS or on a dependent MFMA.
+// Four waves per workgroup, one 32-query block each; two workgroups per compute unit (two waves per SIMD).
 #ifndef DLLM_DENSE_QB
 #define DLLM_DENSE_QB 1
 #endif
 #ifndef DLLM_DENSE_WAVES
-#define DLLM_DENSE_WAVES 8
+#define DLLM_DENSE_WAVES 4
 #endif
 constexpr int kDenseQB = DLLM_DENSE_QB, kDenseWaves = DLLM_DENSE_WAVES;
 

@@ -80,6 +80,30 @@ __device__ __forceinline__ v2u lds_read_tr16(const char* p) {
   return __builtin_bit_cast(v2u, r);
 }
 
+// 16 bytes per lane from global memory straight into LDS (no register in between).  The LDS side is
+// lane-contiguous: lane l's bytes land at LDS byte address lds_wave_base + 16 * l, and lds_wave_base
+// must be the same in every lane of the wave.  Written as inline assembly on purpose: the compiler
+// then does not know that LDS is being written behind its back and does not make the next LDS read
+// wait for the load (it cannot tell ring slots apart and would wait for all of them).  The caller
+// therefore owns the ordering: wait_tile_loads() and then a workgroup barrier before any lane reads
+// what was loaded.  These loads count in vmcnt like any vector memory load.
+__device__ __forceinline__ void load16_to_lds(const void* src, uint32_t lds_wave_base) {
+  asm volatile(
+      "s_mov_b32 m0, %1\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, off"
+      :
+      : "v"(src), "s"(lds_wave_base)
+      : "memory");   // m0 is not tracked by the compiler as an allocatable register; nothing else in these kernels uses it
+}
+// Waits until every load16_to_lds this wave has issued has written its LDS bytes.
+__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// LDS byte address of a pointer into a __shared__ array
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return uint32_t(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)p));
+}
+
 // Per-lane byte offsets for fetching the V^T operand (32 head_dim rows x 16 keys) of one 16-key step
 // out of a row-major V tile.  The first read returns the keys of contraction slots 0..3
 // (key 4*hf + j of the step), the second those of slots 4..7 (8 + 4*hf + j).  base[rd] is for
