@@ -66,6 +66,14 @@ dllm_status check_batch(const dllm_batch* b, dllm::Shape* out) {
   return DLLM_OK;
 }
 
+// The bf16 dense kernel addresses the rows of a 64-key tile with 32-bit byte offsets.
+dllm_status check_dense_strides(const dllm_batch* b) {
+  if (b->dtype == DLLM_BF16 && b->kv_stride_tok * 2 * 64 >= (int64_t(1) << 32))
+    return fail(DLLM_ERR_UNSUPPORTED, "kv_stride_tok %lld is too large for the dense bf16 kernel (64 rows must span < 4 GiB)",
+                static_cast<long long>(b->kv_stride_tok));
+  return DLLM_OK;
+}
+
 dllm_status check_workspace(const void* ws, size_t have, size_t need) {
   if (need == 0) return DLLM_OK;
   if (ws == nullptr) return fail(DLLM_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
@@ -177,6 +185,7 @@ dllm_status dllm_hcsa_attend(const dllm_batch* batch, const int32_t* idx, const 
   if (cu_k == nullptr && (total_k > 0 || seq_mode == nullptr))
     return fail(DLLM_ERR_INVALID_ARG, "cu_k may be NULL only when every sequence is flagged dense");
   if (idx == nullptr && total_k > 0) return fail(DLLM_ERR_INVALID_ARG, "idx is NULL but total_k is %d", total_k);
+  if (seq_mode != nullptr && (st = check_dense_strides(batch)) != DLLM_OK) return st;
   const dllm::AttendPlan plan = dllm::plan_attend(s, batch->dtype, max_k);
   if ((st = check_workspace(workspace, workspace_bytes, plan.bytes)) != DLLM_OK) return st;
   g_err[0] = 0;
@@ -215,6 +224,7 @@ dllm_status dllm_dense_refresh_attend(const dllm_batch* batch, void* o, void* wo
   if (st != DLLM_OK) return st;
   if (o == nullptr) return fail(DLLM_ERR_INVALID_ARG, "o must be non-NULL");
   if (!aligned16(o)) return fail(DLLM_ERR_INVALID_ARG, "o must be 16-byte aligned");
+  if ((st = check_dense_strides(batch)) != DLLM_OK) return st;
   g_err[0] = 0;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipError_t e;

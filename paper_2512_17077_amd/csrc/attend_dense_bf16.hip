@@ -30,6 +30,16 @@
 
 #include "attn_tile.h"
 
+#ifdef DLLM_TIMING
+__device__ unsigned long long g_dense_dbg[8192 * 8];
+extern "C" int dllm_debug_fetch(void* dst, size_t nbytes) {
+  return int(hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dense_dbg), nbytes < sizeof(g_dense_dbg) ? nbytes : sizeof(g_dense_dbg)));
+}
+#define DBG_T(slot) if (threadIdx.x == 0) g_dense_dbg[dbg_wg * 8 + slot] = wall_clock64()
+#else
+#define DBG_T(slot)
+#endif
+
 namespace dllm {
 
 constexpr int kDenseK = 64;          // keys per LDS tile
@@ -64,6 +74,10 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   // times, while consecutive (sequence, head) pairs still go to different XCDs.
   const int nx = gridDim.x, groups = gridDim.y * gridDim.z;
   const int n = blockIdx.x + nx * (blockIdx.y + gridDim.y * blockIdx.z);
+#ifdef DLLM_TIMING
+  const int dbg_wg = n < 8192 ? n : 8191;
+  DBG_T(0);
+#endif
   int qtile = blockIdx.x, gi = blockIdx.y + gridDim.y * blockIdx.z;
   if ((groups & 7) == 0) {
     const int j = n >> 3;   // position in this XCD's own launch sequence
@@ -88,23 +102,6 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     return;
   }
 
-  // Q^T operands: lane (col = query, hf) holds zscale * Q[query][16t + 8hf .. +8) for every step t
-  const float zscale = s.scale * kLog2e;   // > 0
-  v4u qreg[NQB][NT];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int qi = qbase + (wave * NQB + qb) * 32 + col;
-    const uint16_t* qp = q + int64_t(q0 + qi) * s.q_tok + int64_t(h) * s.q_head;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      v4u x = v4u{0u, 0u, 0u, 0u};
-      if (qi < nq) x = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
-      qreg[qb][t] = v4u{cvt_pk_bf16(bf16_lo(x.x) * zscale, bf16_hi(x.x) * zscale),
-                        cvt_pk_bf16(bf16_lo(x.y) * zscale, bf16_hi(x.y) * zscale),
-                        cvt_pk_bf16(bf16_lo(x.z) * zscale, bf16_hi(x.z) * zscale),
-                        cvt_pk_bf16(bf16_lo(x.w) * zscale, bf16_hi(x.w) * zscale)};
-    }
-  }
   const char* kbase = reinterpret_cast<const char*>(k + int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head);
   const char* vbase = reinterpret_cast<const char*>(v + int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head);
   const int64_t pitch = s.kv_tok * 2;
@@ -127,22 +124,56 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   // byte 16 * f, i.e. row f / CH, chunk slot f % CH, and must hold chunk (slot ^ swizzle(row)) of
   // that row.  Rows past the end of the sequence re-read its last row (their keys are masked).
   int ld_row[NLD], ld_col[NLD];
+  uint32_t ld_off[NLD];   // byte offset of the chunk from the tile's first row (fits: checked on the host)
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
     const int f = i * NTHREADS + tid, row = f / CH;
     ld_row[i] = row;
     ld_col[i] = ((f % CH) ^ tile_swz<D>(row)) << 4;
+    ld_off[i] = uint32_t(row) * uint32_t(pitch) + uint32_t(ld_col[i]);
   }
   // this wave's slice of each load round, as an LDS byte address
   const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 64 * 16);
   auto load_tile = [&](const char* base, int tile, int lds_off) {
     const int t0 = tile * kDenseK;
+    if (t0 + kDenseK <= L) {   // whole tile inside the sequence: uniform tile address + fixed lane offsets
+      const char* tbase = base + int64_t(t0) * pitch;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int row = min(t0 + ld_row[i], L - 1);
-      load16_to_lds(base + row * pitch + ld_col[i], wave_lds + lds_off + i * NTHREADS * 16);
+      for (int i = 0; i < NLD; ++i) load16_to_lds(tbase, ld_off[i], wave_lds + lds_off + i * NTHREADS * 16);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int row = min(t0 + ld_row[i], L - 1);
+        load16_to_lds(base + row * pitch + ld_col[i], wave_lds + lds_off + i * NTHREADS * 16);
+      }
     }
   };
+
+  // the first tiles are requested before anything else, so their latency overlaps the Q loads
+  const int rem = L % 32;
+  const int nsteps = L / 32 + (rem ? 1 : 0);
+  const int ntiles = (L + kDenseK - 1) / kDenseK;
+  load_tile(kbase, 0, 0);
+  load_tile(vbase, 0, VBASE);
+  if (ntiles > 1) load_tile(kbase, 1, TILEB);
+
+  // Q^T operands: lane (col = query, hf) holds zscale * Q[query][16t + 8hf .. +8) for every step t
+  const float zscale = s.scale * kLog2e;   // > 0
+  v4u qreg[NQB][NT];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int qi = qbase + (wave * NQB + qb) * 32 + col;
+    const uint16_t* qp = q + int64_t(q0 + qi) * s.q_tok + int64_t(h) * s.q_head;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      v4u x = v4u{0u, 0u, 0u, 0u};
+      if (qi < nq) x = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
+      qreg[qb][t] = v4u{cvt_pk_bf16(bf16_lo(x.x) * zscale, bf16_hi(x.x) * zscale),
+                        cvt_pk_bf16(bf16_lo(x.y) * zscale, bf16_hi(x.y) * zscale),
+                        cvt_pk_bf16(bf16_lo(x.z) * zscale, bf16_hi(x.z) * zscale),
+                        cvt_pk_bf16(bf16_lo(x.w) * zscale, bf16_hi(x.w) * zscale)};
+    }
+  }
 
   // running maximum m (base-2 logits), kept negated in all 16 registers of an accumulator so that
   // it can seed the score MFMA chain; row sum; output accumulators
@@ -160,18 +191,23 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       for (int i = 0; i < 16; ++i) acc[qb][db][i] = 0.0f;
   }
 
-  // scores of the 32-key step at byte offset `koff` of the K ring, relative to the running maxima:
-  // rows = keys, columns = this wave's queries
-  auto scores = [&](f32x16 (&st)[NQB], int koff) {
+  // A operands of one step's score chain: rows = 32 keys at byte offset `koff` of the K ring
+  auto k_operands = [&](v4u (&kop)[NT], int koff) {
+#pragma unroll
+#ifdef DLLM_ABL_NOLDSREAD
+    for (int t = 0; t < NT; ++t) kop[t] = qreg[0][(t + 1) % NT];
+#else
+    for (int t = 0; t < NT; ++t) kop[t] = *reinterpret_cast<const v4u*>(smem + ka[t] + koff);
+#endif
+  };
+  // scores of a 32-key step relative to the running maxima: rows = keys, columns = this wave's queries
+  auto score_chain = [&](f32x16 (&st)[NQB], const v4u (&kop)[NT]) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) st[qb] = negm[qb];
-    v4u a[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) a[t] = *reinterpret_cast<const v4u*>(smem + ka[t] + koff);
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) st[qb] = mfma_bf16(a[t], qreg[qb][t], st[qb]);
+      for (int qb = 0; qb < NQB; ++qb) st[qb] = mfma_bf16(kop[t], qreg[qb][t], st[qb]);
   };
   auto mask_tail = [&](f32x16 (&st)[NQB], int nvalid) {   // keys past the end get no weight
     asm volatile("" ::: "memory");   // keep the caller's test a real (uniform) branch
@@ -215,40 +251,50 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       uint32_t w[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
+#ifdef DLLM_ABL_NOEXP
+        const float p0 = st[qb][8 * u + 2 * j], p1 = st[qb][8 * u + 2 * j + 1];
+#else
         const float p0 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j]);
         const float p1 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j + 1]);
+#endif
         w[j] = cvt_pk_bf16(p0, p1);
         lsum[qb] = add_pair_bf16(w[j], lsum[qb]);
       }
       pb[qb] = v4u{w[0], w[1], w[2], w[3]};
     }
   };
-  auto accumulate = [&](int voff, const v4u (&pb)[NQB]) {
-    v4u a[NDB];
+  // A operands of one 16-key slice of O^T += V^T P^T: V^T blocks of 32 head_dim rows x 16 keys
+  auto v_operands = [&](v4u (&vop)[NDB], int voff) {
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
+#ifdef DLLM_ABL_NOLDSREAD
+      vop[db] = qreg[0][db];
+#else
       const v2u lo = lds_read_tr16(smem + va[0][db] + voff);
       const v2u hi = lds_read_tr16(smem + va[1][db] + voff);
-      a[db] = v4u{lo.x, lo.y, hi.x, hi.y};
+      vop[db] = v4u{lo.x, lo.y, hi.x, hi.y};
+#endif
     }
+  };
+  auto accumulate = [&](const v4u (&vop)[NDB], const v4u (&pb)[NQB]) {
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) acc[qb][db] = mfma_bf16(a[db], pb[qb], acc[qb][db]);
+      for (int qb = 0; qb < NQB; ++qb) acc[qb][db] = mfma_bf16(vop[db], pb[qb], acc[qb][db]);
   };
 
-  const int rem = L % 32;
-  const int nsteps = L / 32 + (rem ? 1 : 0);
-  const int ntiles = (L + kDenseK - 1) / kDenseK;
-
-  load_tile(kbase, 0, 0);
-  load_tile(vbase, 0, VBASE);
-  if (ntiles > 1) load_tile(kbase, 1, TILEB);
   wait_tile_loads();
   __syncthreads();
 
+  // Issue-order hints: inside a stage, spread the vector and LDS work between the MFMAs so that the
+  // matrix pipe always has the next MFMA waiting behind work that does not depend on it.
+#define DLLM_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+  constexpr int kMfma = 0x008, kValu = 0x002, kTrans = 0x400, kDsRead = 0x100;
+
   f32x16 st_a[NQB], st_b[NQB];
-  scores(st_a, 0);
+  v4u kop[NT];   // K operands of the next score chain, fetched a stage ahead of their use
+  k_operands(kop, 0);
+  score_chain(st_a, kop);
   if (nsteps == 1 && rem) mask_tail(st_a, rem);
   {   // the first step sets the maxima outright (they may be negative)
     float delta[NQB];
@@ -256,33 +302,73 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     for (int qb = 0; qb < NQB; ++qb) delta[qb] = max_across_halves(lane_max(st_a[qb]));
     raise(st_a, delta);
   }
+  k_operands(kop, 32 * ROWB);   // step 1 (stale LDS if there is none; then unused)
 
   // One 32-key step.  R is its position in the common turn of the rings, which fixes every LDS
-  // offset: the step reads V tile (R/2) % 2, half R%2, and computes the scores of the step after it.
+  // offset.  The step multiplies P of step i with V tile (R/2) % 2, half R%2, computes the scores of
+  // step i+1 from K operands fetched during step i-1, and fetches those of step i+2.
+  DBG_T(1);
+#ifdef DLLM_TIMING
+  unsigned long long dbg_vm = 0, dbg_bar = 0;
+  if (threadIdx.x == 0) g_dense_dbg[dbg_wg * 8 + 4] = __builtin_readcyclecounter();
+#endif
   int i = 0;
   auto step = [&](auto rc, f32x16 (&cur)[NQB], f32x16 (&nxt)[NQB]) {
     constexpr int R = decltype(rc)::value;
     constexpr int T = R / 2, kb = R % 2;   // tile index modulo the turn
-    constexpr int RN = (R + 1) % ROUND;
+    constexpr int RN2 = (R + 2) % ROUND;
     const int tile = i >> 1;
     if (kb == 0) {
       // Tile boundary: everyone is done with tile-1, and the loads issued a tile ago (K of tile+1,
       // V of this tile) have landed.  The slots of tile-1 take K of tile+2 and V of tile+1.
+#ifdef DLLM_TIMING
+      const unsigned long long tw0 = wall_clock64();
+      wait_tile_loads();
+      const unsigned long long tw1 = wall_clock64();
+      __syncthreads();
+      const unsigned long long tw2 = wall_clock64();
+      dbg_vm += tw1 - tw0;
+      dbg_bar += tw2 - tw1;
+#elif defined(DLLM_ABL_NOSYNC)
+#else
       wait_tile_loads();
       __syncthreads();
+#endif
+#ifndef DLLM_ABL_NOLOAD
       if (tile + 2 < ntiles) load_tile(kbase, tile + 2, ((T + 2) % kDenseRingK) * TILEB);
       if (tile + 1 < ntiles) load_tile(vbase, tile + 1, VBASE + ((T + 1) % kDenseRingV) * TILEB);
+#endif
     }
     constexpr int voff = (T % kDenseRingV) * TILEB + kb * 32 * ROWB;
-    v4u pb0[NQB], pb1[NQB];
-    // stage 1 (past the last step the scores are computed from stale LDS and never used)
-    scores(nxt, ((RN / 2) % kDenseRingK) * TILEB + (RN % 2) * 32 * ROWB);
+    v4u pb0[NQB], pb1[NQB], vop0[NDB], vop1[NDB];
+    __builtin_amdgcn_sched_barrier(0);
+    // stage 1: S^T(i+1) chain || exp2 of keys 0..15 of step i || fetch V^T operands of keys 0..15
+    v_operands(vop0, voff);
+    score_chain(nxt, kop);
     probs(cur, 0, pb0);
-    // stage 2
-    accumulate(voff, pb0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {   // one group per pair of probabilities packed together
+      DLLM_SGB(kMfma, NT * NQB / 4);
+      DLLM_SGB(kDsRead, 2 * NDB / 4);
+      DLLM_SGB(kTrans, 2 * NQB);
+      DLLM_SGB(kValu, 2 * NQB);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // stage 2: O^T += V^T P^T, keys 0..15 || exp2 of keys 16..31 || fetch V^T operands of keys 16..31
+    v_operands(vop1, voff + 16 * ROWB);
+    accumulate(vop0, pb0);
     probs(cur, 1, pb1);
-    // stage 3
-    accumulate(voff + 16 * ROWB, pb1);
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      DLLM_SGB(kMfma, NQB);
+      DLLM_SGB(kDsRead, 2);
+      DLLM_SGB(kTrans, 8 * NQB / NDB);
+      DLLM_SGB(kValu, 8 * NQB / NDB);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // stage 3: O^T += V^T P^T, keys 16..31 || row maxima of step i+1 || fetch K operands of step i+2
+    k_operands(kop, ((RN2 / 2) % kDenseRingK) * TILEB + (RN2 % 2) * 32 * ROWB);
+    accumulate(vop1, pb1);
     bool grow = false;
     float mx[NQB];
 #pragma unroll
@@ -290,6 +376,13 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       mx[qb] = lane_max(nxt[qb]);
       grow = grow || (mx[qb] > kLazyStep);
     }
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      DLLM_SGB(kMfma, NQB);
+      DLLM_SGB(kDsRead, NT / NDB);
+      DLLM_SGB(kValu, 3 * NQB);
+    }
+    __builtin_amdgcn_sched_barrier(0);
     ++i;
     // Rare path, one uniform branch: the next step is the ragged last one (mask the keys past the end,
     // which were scored from a repeated row), or some score outgrew its running maximum.
@@ -333,6 +426,11 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     step(std::integral_constant<int, 11>{}, st_b, st_a);
   }
 
+  DBG_T(2);
+#ifdef DLLM_TIMING
+  if (threadIdx.x == 0) g_dense_dbg[dbg_wg * 8 + 5] = __builtin_readcyclecounter();
+  if (threadIdx.x == 0) { g_dense_dbg[dbg_wg * 8 + 6] = dbg_vm; g_dense_dbg[dbg_wg * 8 + 7] = dbg_bar; }
+#endif
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int qi = qbase + (wave * NQB + qb) * 32 + col;
@@ -352,6 +450,7 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       }
     }
   }
+  DBG_T(3);
 }
 
 // Four waves per workgroup, one 32-query block each; two workgroups per compute unit (two waves per SIMD).

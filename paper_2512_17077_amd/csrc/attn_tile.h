@@ -96,6 +96,17 @@ __device__ __forceinline__ void load16_to_lds(const void* src, uint32_t lds_wave
       : "v"(src), "s"(lds_wave_base)
       : "memory");   // m0 is not tracked by the compiler as an allocatable register; nothing else in these kernels uses it
 }
+// Same, with the global address given as a wave-uniform base plus a 32-bit per-lane byte offset (no
+// vector arithmetic on 64-bit addresses).
+__device__ __forceinline__ void load16_to_lds(const void* uniform_base, uint32_t lane_off, uint32_t lds_wave_base) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(lane_off), "s"(uniform_base), "s"(lds_wave_base)
+      : "memory");
+}
 // Waits until every load16_to_lds this wave has issued has written its LDS bytes.
 __device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
