@@ -74,6 +74,18 @@ dllm_status check_dense_strides(const dllm_batch* b) {
   return DLLM_OK;
 }
 
+// The bf16 gather kernel addresses the kept rows of a sequence with 32-bit byte offsets from the
+// sequence's first row, computed with a 24-bit multiply.
+dllm_status check_sparse_strides(const dllm_batch* b) {
+  if (b->dtype != DLLM_BF16) return DLLM_OK;
+  const int64_t pitch = b->kv_stride_tok * 2;
+  if (pitch >= (int64_t(1) << 24) || int64_t(b->max_kv) * pitch >= (int64_t(1) << 32))
+    return fail(DLLM_ERR_UNSUPPORTED,
+                "one sequence's K/V rows must span < 4 GiB with a token stride < 16 MiB for the bf16 gather kernel "
+                "(max_kv=%d, kv_stride_tok=%lld)", b->max_kv, static_cast<long long>(b->kv_stride_tok));
+  return DLLM_OK;
+}
+
 dllm_status check_workspace(const void* ws, size_t have, size_t need) {
   if (need == 0) return DLLM_OK;
   if (ws == nullptr) return fail(DLLM_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
@@ -186,6 +198,7 @@ dllm_status dllm_hcsa_attend(const dllm_batch* batch, const int32_t* idx, const 
     return fail(DLLM_ERR_INVALID_ARG, "cu_k may be NULL only when every sequence is flagged dense");
   if (idx == nullptr && total_k > 0) return fail(DLLM_ERR_INVALID_ARG, "idx is NULL but total_k is %d", total_k);
   if (seq_mode != nullptr && (st = check_dense_strides(batch)) != DLLM_OK) return st;
+  if (total_k > 0 && (st = check_sparse_strides(batch)) != DLLM_OK) return st;
   const dllm::AttendPlan plan = dllm::plan_attend(s, batch->dtype, max_k);
   if ((st = check_workspace(workspace, workspace_bytes, plan.bytes)) != DLLM_OK) return st;
   g_err[0] = 0;

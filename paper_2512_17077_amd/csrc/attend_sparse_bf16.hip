@@ -2,12 +2,15 @@
 // Section 4.5), bf16 inputs, fp32 softmax state and accumulators, on the gfx950 matrix cores.
 //
 // The step is bound by HBM: every kept (head, row) pair costs one 2*D-byte K row and one V row and
-// only 4*Bq*D flop.  A workgroup of four waves walks one chunk of one (sequence, head)'s kept rows;
-// each wave owns its own 32-row tiles, so no workgroup barrier sits in the loop:
-//   gather   idx -> row addresses; 16-byte loads with a row's chunks in neighbouring lanes (whole
-//            256-byte rows per 16 lanes), prefetched one tile ahead into registers
-//   stage    registers -> the wave's private LDS tile, XOR-swizzled by row
-//   S^T      = K_tile (32 keys x D) * Q^T (D x 32 queries): A by ds_read_b128, B = Q in registers
+// only 4*Bq*D flop.  What decides its speed is how many gathered rows are in flight, so the registers
+// go to the gathers: a workgroup of four waves walks one chunk of one (sequence, head)'s kept rows,
+// each wave owns its own 32-row tiles (no workgroup barrier in the loop) and keeps TWO tiles of K and
+// V rows in flight in registers; the queries, which every step needs again, live in LDS instead.
+//   gather   idx -> row offsets (32-bit, from a uniform base); 16-byte non-temporal loads with a row's
+//            chunks in neighbouring lanes (whole 256-byte rows per 16 lanes)
+//   stage    registers -> the wave's private LDS tile, XOR-swizzled by row; the freed registers are
+//            refilled with the tile after next at once
+//   S^T      = K_tile (32 keys x D) * Q^T (D x 32 queries): A and B by ds_read_b128
 //   softmax  online, base 2, lazily rescaled, per query column
 //   O^T     += V_tile^T * P^T: A by ds_read_b64_tr_b16, B = the S^T accumulators in place
 // After the loop the four waves merge (m, l, O) through LDS.  A (sequence, head) whose kept rows fit
@@ -20,6 +23,10 @@ constexpr int kTile = 32;        // kept rows per wave tile
 constexpr int kWaves = 4;
 constexpr float kLazyStepS = 8.0f;
 constexpr int kMaxTilesPerWave = 16;  // chunk_rows <= kMaxTilesPerWave * kWaves * kTile
+#ifndef DLLM_SPARSE_DEPTH
+#define DLLM_SPARSE_DEPTH 1
+#endif
+constexpr int kDepth = DLLM_SPARSE_DEPTH;   // tiles of gathered rows a wave keeps in flight in registers
 constexpr int kRankBatch = 64;        // batches up to this size are walked longest kept list first
 
 // A (sequence, head) with kb kept rows is cut into n = ceil(kb / chunk_rows) chunks of equal size
@@ -94,7 +101,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
 
   // per wave: K tile then V tile; reused as fp32 merge space afterwards
   __shared__ __attribute__((aligned(16))) char lds[kWaves][2 * TILEB];
-  __shared__ float sm_m[kWaves][32], sm_l[kWaves][32];
+  // the 32 queries of the current query tile (same swizzled layout as a K tile); after the loop the
+  // waves' (m, l) pairs are exchanged through it
+  __shared__ __attribute__((aligned(16))) char qtile[TILEB];
   __shared__ int sm_rows[kWaves][kMaxTilesPerWave * kTile];   // kept-row ids of each wave's tiles
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -122,7 +131,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
   const int32_t* __restrict__ rows = idx + int64_t(h) * total_k + ko0;
   const char* kbase = reinterpret_cast<const char*>(k + int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head);
   const char* vbase = reinterpret_cast<const char*>(v + int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head);
-  const int64_t pitch = s.kv_tok * 2;
+  const uint32_t pitch = uint32_t(s.kv_tok) * 2u;   // a sequence's K spans < 4 GiB (checked on the host)
   const float zscale = s.scale * kLog2e;
   const int ntiles = (c1 - c0 + kTile - 1) / kTile;
   char* ktile = lds[wave];
@@ -132,24 +141,27 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
   ka.init(lane);
   VtAddr<D> vt;
   vt.init(lane);
-  int woff[NLD];
-#pragma unroll
-  for (int i = 0; i < NLD; ++i) {
-    const int f = i * 64 + lane;
-    woff[i] = tile_off<D>(f / CH, f % CH);
-  }
-  const int coff = (lane % CH) * 16;   // this lane's byte offset inside a gathered row
+  const uint32_t coff = (lane % CH) * 16;   // this lane's byte offset inside a gathered row
+  // Registers are what bounds the number of gathered rows in flight, so per-lane LDS offsets are not
+  // kept in registers across the loop: each round derives them again (one XOR each) from three values
+  // it first passes through opaque(), which keeps the compiler from hoisting the derived ones.
+  auto opaque = [](int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+  };
 
   for (int qt = 0; qt * 32 < nq; ++qt) {
-    // Q^T operand: lane (col = query, hf) holds Q[query][16t + 8hf .. +8) for every step t
-    v4u qreg[NT];
+    // Q tile -> LDS: thread f takes chunk f % CH of query row f / CH (zeros past the last query)
     {
-      const int qi = qt * 32 + col;
-      const uint16_t* qp = q + int64_t(q0 + qi) * s.q_tok + int64_t(h) * s.q_head;
+      constexpr int NQL = kTile * CH / (kWaves * 64);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        qreg[t] = v4u{0u, 0u, 0u, 0u};
-        if (qi < nq) qreg[t] = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
+      for (int i = 0; i < NQL; ++i) {
+        const int f = i * kWaves * 64 + threadIdx.x, r = f / CH, c = f % CH;
+        const int qi = qt * 32 + r;
+        v4u x = v4u{0u, 0u, 0u, 0u};
+        if (qi < nq)
+          x = *reinterpret_cast<const v4u*>(q + int64_t(q0 + qi) * s.q_tok + int64_t(h) * s.q_head + c * 8);
+        *reinterpret_cast<v4u*>(qtile + tile_off<D>(r, c)) = x;
       }
     }
     float m_used = -INFINITY, lsum = 0.0f;
@@ -159,7 +171,6 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[db][i] = 0.0f;
 
-    v4u kr[NLD], vr[NLD];
     // Kept-row ids of every tile this wave will walk go to LDS once (positions past the end repeat
     // the last kept row; such rows are masked out of the softmax below).
     int* my_rows = sm_rows[wave];
@@ -169,28 +180,31 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
       const int t = min(c0 + (wave + (slot >> 5) * kWaves) * kTile + (slot & 31), c1 - 1);
       my_rows[slot] = rows[t];
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    auto fetch = [&](int j) {   // gather the wave's j-th tile into registers
+    __syncthreads();   // Q tile and row ids are in place
+    // gather the wave's j-th tile into a register buffer
+    auto fetch = [&](v4u (&kr)[NLD], v4u (&vr)[NLD], int j) {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int64_t r = my_rows[j * kTile + (i * 64 + lane) / CH];
-        kr[i] = load_once(kbase + r * pitch + coff);
-        vr[i] = load_once(vbase + r * pitch + coff);
+        const uint32_t off = __umul24(uint32_t(my_rows[j * kTile + (i * 64 + lane) / CH]), pitch) + coff;
+        kr[i] = load_once(kbase + off);
+        vr[i] = load_once(vbase + off);
       }
     };
-
-    int tile = wave;
-    if (tile < ntiles) fetch(0);
-
-    for (int j = 0; tile < ntiles; ++j, tile += kWaves) {
+    // one tile: registers -> LDS, refill the registers with the tile after next, then the math
+    auto round = [&](v4u (&kr)[NLD], v4u (&vr)[NLD], int j, int tile) {
+      KAddr<D> kar;
+      kar.base = opaque(ka.base);
+      VtAddr<D> vtr;
+      vtr.base[0] = opaque(vt.base[0]);
+      vtr.base[1] = opaque(vt.base[1]);
+      const int lane_o = opaque(lane);
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        *reinterpret_cast<v4u*>(ktile + woff[i]) = kr[i];
-        *reinterpret_cast<v4u*>(vtile + woff[i]) = vr[i];
+        const int f = i * 64 + lane_o, woff = tile_off<D>(f / CH, f % CH);
+        *reinterpret_cast<v4u*>(ktile + woff) = kr[i];
+        *reinterpret_cast<v4u*>(vtile + woff) = vr[i];
       }
-      if (tile + kWaves < ntiles) fetch(j + 1);
+      if (tile + kDepth * kWaves < ntiles) fetch(kr, vr, j + kDepth);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -201,7 +215,15 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
       for (int i = 0; i < 16; ++i) st[i] = 0.0f;
 #pragma unroll
       for (int t = 0; t < NT; ++t)
-        st = mfma_bf16(*reinterpret_cast<const v4u*>(ktile + ka.off(t)), qreg[t], st);
+        st = mfma_bf16(*reinterpret_cast<const v4u*>(ktile + kar.off(t)),
+                       *reinterpret_cast<const v4u*>(qtile + kar.off(t)), st);
+      // issue order: operand fetches just ahead of their MFMA, so few operand registers are live
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 
       const int nvalid = c1 - (c0 + tile * kTile);
       if (nvalid < kTile) {
@@ -231,53 +253,88 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
       for (int u = 0; u < 2; ++u) {
         uint32_t w[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * j], zscale, neg_m));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * j + 1], zscale, neg_m));
-          w[j] = cvt_pk_bf16(p0, p1);
-          lsum = add_pair_bf16(w[j], lsum);
+        for (int jj = 0; jj < 4; ++jj) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * jj], zscale, neg_m));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * jj + 1], zscale, neg_m));
+          w[jj] = cvt_pk_bf16(p0, p1);
+          lsum = add_pair_bf16(w[jj], lsum);
         }
         pb[u] = v4u{w[0], w[1], w[2], w[3]};
       }
       // O^T += V^T P^T, 16 keys per step
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-          const v2u lo = lds_read_tr16(vtile + vt.off(0, db) + 16 * u * ROWB);
-          const v2u hi = lds_read_tr16(vtile + vt.off(1, db) + 16 * u * ROWB);
+          const v2u lo = lds_read_tr16(vtile + vtr.off(0, db) + 16 * u * ROWB);
+          const v2u hi = lds_read_tr16(vtile + vtr.off(1, db) + 16 * u * ROWB);
           acc[db] = mfma_bf16(v4u{lo.x, lo.y, hi.x, hi.y}, pb[u], acc[db]);
         }
+#pragma unroll
+      for (int i = 0; i < 2 * NDB; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
       __builtin_amdgcn_wave_barrier();
+    };
+
+    if constexpr (kDepth == 2) {
+      v4u kra[NLD], vra[NLD], krb[NLD], vrb[NLD];
+      int tile = wave, j = 0;
+      if (tile < ntiles) fetch(kra, vra, 0);
+      if (tile + kWaves < ntiles) fetch(krb, vrb, 1);
+      while (tile < ntiles) {
+        round(kra, vra, j, tile);
+        tile += kWaves;
+        ++j;
+        if (tile >= ntiles) break;
+        round(krb, vrb, j, tile);
+        tile += kWaves;
+        ++j;
+      }
+    } else {
+      v4u kra[NLD], vra[NLD];
+      int tile = wave;
+      if (tile < ntiles) fetch(kra, vra, 0);
+      for (int j = 0; tile < ntiles; ++j, tile += kWaves) round(kra, vra, j, tile);
     }
 
     // ---- merge the four waves' (m, l, O^T) through LDS
     const float l = sum_across_halves(lsum);
-    __syncthreads();                       // every wave is done with its tile buffers
-    if (hf == 0) { sm_m[wave][col] = m_used; sm_l[wave][col] = l; }
+    float* sm_m = reinterpret_cast<float*>(qtile);           // [wave][32]
+    float* sm_l = reinterpret_cast<float*>(qtile) + kWaves * 32;
+    __syncthreads();                       // every wave is done with its tile buffers and with Q
+    if (hf == 0) { sm_m[wave * 32 + col] = m_used; sm_l[wave * 32 + col] = l; }
     __syncthreads();
     float m_all = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, sm_m[w][col]);
+    for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, sm_m[w * 32 + col]);
     float l_all = 0.0f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) l_all += sm_l[w][col] * __builtin_amdgcn_exp2f(sm_m[w][col] - m_all);
+    for (int w = 0; w < kWaves; ++w) l_all += sm_l[w * 32 + col] * __builtin_amdgcn_exp2f(sm_m[w * 32 + col] - m_all);
     const float mine = __builtin_amdgcn_exp2f(m_used - m_all);   // 0 for a wave that saw no tile
-    float* mrg = reinterpret_cast<float*>(&lds[0][0]);           // [wave][db][reg][lane]
+    float4* mrg = reinterpret_cast<float4*>(&lds[0][0]);         // [wave][db][quad][lane], 16 bytes per lane
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mrg[((wave * NDB + db) * 16 + i) * 64 + lane] = acc[db][i] * mine;
+      for (int i4 = 0; i4 < 4; ++i4)
+        mrg[((wave * NDB + db) * 4 + i4) * 64 + lane] =
+            make_float4(acc[db][4 * i4 + 0] * mine, acc[db][4 * i4 + 1] * mine, acc[db][4 * i4 + 2] * mine,
+                        acc[db][4 * i4 + 3] * mine);
     __syncthreads();
     if (wave < NDB) {
       const int db = wave;
       float outv[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float a = 0.0f;
+      for (int i4 = 0; i4 < 4; ++i4) {
+        float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) a += mrg[((w * NDB + db) * 16 + i) * 64 + lane];
-        outv[i] = a;
+        for (int w = 0; w < kWaves; ++w) {
+          const float4 x = mrg[((w * NDB + db) * 4 + i4) * 64 + lane];
+          a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w;
+        }
+        outv[4 * i4 + 0] = a.x; outv[4 * i4 + 1] = a.y; outv[4 * i4 + 2] = a.z; outv[4 * i4 + 3] = a.w;
       }
       const int qi = qt * 32 + col;
       if (qi < nq) {
