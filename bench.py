@@ -5,7 +5,8 @@ One "step" is one pass of the whole hot path over resident synthetic inputs:
     select  + attend   on the batched Reuse workload   (16 seqs, KV 512..4096, keep 10..50 %)
     dense Refresh      on the Refresh workload          (8 x L=2048, 32 heads x 128)
     select  + attend   on the mixed GQA burst           (24 Reuse + 8 Refresh sequences in one call)
-All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
+The five calls are interleaved (attend c3, select c5, dense c4, select c3, attend c5) so that every call
+starts with cold caches.  All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
 stream it is launched on; rates are algorithmic bytes (or flops) divided by the mean call duration.
 
 Prints ONE JSON line.  `value` is the Reuse sparse-attention rate in GB/s of algorithmic bytes
@@ -31,15 +32,16 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 # with the commands, is profiles/hbm_traffic_pmc.md.  They are properties of the workload shapes
 # above, not of the timing, so they are recorded here rather than re-measured on every run.
 TRAFFIC_BYTES = {
-    "attend_dense_bf16_kernel": 536.97e6,    # Refresh c4: 402.8 MB read + 134.2 MB written
-    "attend_sparse_bf16_kernel": 205.82e6,   # Reuse c3: 196.9 MB read + 8.9 MB written
-    "score_kernel": 288.09e6,                # Reuse c3: 283.1 MB read + 5.0 MB written
+    "attend_dense_bf16_kernel": 537.4e6,     # Refresh c4: 403.0 MB read + 134.4 MB written
+    "attend_sparse_bf16_kernel": 197.9e6,    # Reuse c3: 193.7 MB read + 4.2 MB written
+    "score_kernel": 287.5e6,                 # Reuse c3: 283.1 MB read + 4.5 MB written
 }
 
 # What plain kernels reach on this GPU (python -m paper_2512_17077_amd.ceilings; profiles/ceilings_microbench.md):
 # context for the fractions of the published peaks, never used as the roofline denominator.
-MEASURED_CEILINGS = {"hbm_stream_read_GBps": 5129.0, "hbm_row_gather_GBps": 4883.0,
-                     "mfma_bf16_sustained_TFLOPs": 2034.0, "shader_clock_under_mfma_MHz": 1993.0}
+MEASURED_CEILINGS = {"hbm_stream_read_grid_stride_GBps": 5226.0, "hbm_stream_read_spans_nontemporal_GBps": 6572.0,
+                     "hbm_row_gather_GBps": 4822.0, "mfma_bf16_sustained_TFLOPs": 2012.0,
+                     "shader_clock_under_mfma_MHz": 1965.0}
 
 
 def parse():
@@ -134,15 +136,32 @@ def main():
     ws5s = ws(hcsa.dllm_hcsa_select_workspace(d5.batch, d5.max_k))
     ws5a = ws(hcsa.dllm_hcsa_attend_workspace(d5.batch, d5.max_k))
 
+    # Call order inside a step: no call follows one that touched its inputs, so every call starts
+    # with cold caches (the 256 MB memory-side cache would otherwise serve, e.g., the K rows that the
+    # Reuse attend gathers right after selection streamed them).  In serving, selection runs at Refresh
+    # steps only and a Reuse attend finds other layers' data in the caches, never its own.
+    sel3 = Timed("select_reuse", lambda: d3.select(workspace=ws3s))
+    att3 = Timed("attend_reuse", lambda: d3.attend(workspace=ws3a))
+    den4 = Timed("dense_refresh", lambda: d4.dense_refresh())
+    sel5 = Timed("select_mixed", lambda: d5.select(workspace=ws5s))
+    att5 = Timed("attend_mixed", lambda: d5.attend(workspace=ws5a))
     calls = []
     if args.only in ("all", "reuse"):
-        calls += [Timed("select_reuse", lambda: d3.select(workspace=ws3s)),
-                  Timed("attend_reuse", lambda: d3.attend(workspace=ws3a))]
-    if args.only in ("all", "refresh"):
-        calls += [Timed("dense_refresh", lambda: d4.dense_refresh())]
+        calls += [att3]
     if args.only in ("all", "mixed"):
-        calls += [Timed("select_mixed", lambda: d5.select(workspace=ws5s)),
-                  Timed("attend_mixed", lambda: d5.attend(workspace=ws5a))]
+        calls += [sel5]
+    if args.only in ("all", "refresh"):
+        calls += [den4]
+    if args.only in ("all", "reuse"):
+        calls += [sel3]
+    if args.only in ("all", "mixed"):
+        calls += [att5]
+    # the kept-row indices the first attend calls read
+    if args.only in ("all", "reuse"):
+        d3.select(workspace=ws3s)
+    if args.only in ("all", "mixed"):
+        d5.select(workspace=ws5s)
+    torch.cuda.synchronize()
 
     if args.copy_probe:
         # one plain elementwise pass of known size: reads 1 GiB, writes 1 GiB (dst = src + 1 on int32)

@@ -1,7 +1,8 @@
 // Measured ceilings of one MI355X for the two rooflines this library is held to.  Stand-alone
 // program (no part of the library): prints what a plain kernel achieves for
 //   (a) streaming reads from HBM, no reuse between launches (each launch reads another 512 MiB
-//       window of a 6 GiB buffer, so neither L2 nor the 256 MB memory-side cache helps),
+//       window of a 6 GiB buffer, so neither L2 nor the 256 MB memory-side cache helps), once with a
+//       grid-stride loop and once with a contiguous span per workgroup and non-temporal loads,
 //   (b) gathers of 256-byte rows at an 8 KiB token stride, 32 heads active, kept rows random at
 //       33 % density and ascending -- the access pattern of Reuse-phase attention,
 //   (c) back-to-back v_mfma_f32_32x32x16_bf16 with independent accumulators, with the shader clock
@@ -36,6 +37,22 @@ __global__ __launch_bounds__(256) void stream_read(const uint4* __restrict__ p, 
     acc.z ^= a.z ^ b.z ^ c.z ^ d.z; acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
   }
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) out[0] = 1;   // keeps the loads alive
+}
+
+// each workgroup reads one contiguous span, eight non-temporal 16-byte loads per lane in flight
+typedef __attribute__((ext_vector_type(4))) unsigned int v4u;
+__global__ __launch_bounds__(256) void stream_read_spans(const v4u* __restrict__ p, size_t n16, unsigned* out) {
+  const size_t per_block = n16 / gridDim.x;
+  const v4u* q = p + (size_t)blockIdx.x * per_block;
+  v4u acc = {0, 0, 0, 0};
+  for (size_t i = threadIdx.x; i + 7 * 256 < per_block; i += 8 * 256) {
+    v4u r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = __builtin_nontemporal_load(q + i + j * 256);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= r[j];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) out[0] = 1;
 }
 
 // wave -> (head, list of rows); NL 16-byte loads per lane in flight, four rows per load instruction
@@ -91,7 +108,17 @@ int main() {
       float ms; CK(hipEventElapsedTime(&ms, a, b));
       if (w >= 2) { tot += ms; ++reps; }
     }
-    printf("stream_read: %.1f us per 512 MiB -> %.0f GB/s\n", tot / reps * 1e3, 536.870912 / (tot / reps));
+    printf("stream_read (grid-stride loop): %.1f us per 512 MiB -> %.0f GB/s\n", tot / reps * 1e3, 536.870912 / (tot / reps));
+    tot = 0; reps = 0;
+    for (int w = 0; w < nwin; ++w) {
+      CK(hipEventRecord(a));
+      stream_read_spans<<<8192, 256>>>((const v4u*)(d_buf + (long)w * win_tokens * pitch), win_tokens * pitch / 16, d_out);
+      CK(hipEventRecord(b)); CK(hipEventSynchronize(b));
+      float ms; CK(hipEventElapsedTime(&ms, a, b));
+      if (w >= 2) { tot += ms; ++reps; }
+    }
+    printf("stream_read (contiguous span per workgroup, non-temporal loads): %.1f us per 512 MiB -> %.0f GB/s\n", tot / reps * 1e3,
+           536.870912 / (tot / reps));
   }
   {  // (b)
     std::mt19937 rng(7);
