@@ -5,8 +5,9 @@ One "step" is one pass of the whole hot path over resident synthetic inputs:
     select  + attend   on the batched Reuse workload   (16 seqs, KV 512..4096, keep 10..50 %)
     dense Refresh      on the Refresh workload          (8 x L=2048, 32 heads x 128)
     select  + attend   on the mixed GQA burst           (24 Reuse + 8 Refresh sequences in one call)
-The five calls are interleaved (attend c3, select c5, dense c4, select c3, attend c5) so that every call
-starts with cold caches.  All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
+plus the paper's own Reuse layout on the first workload: pack the kept rows once, attend over the packed cache.
+The calls are interleaved (attend c3, select c5, pack c3, dense c4, select c3, packed attend c3, attend c5)
+so that every call starts with cold caches.  All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
 stream it is launched on; rates are algorithmic bytes (or flops) divided by the mean call duration.
 
 Prints ONE JSON line.  `value` is the Reuse sparse-attention rate in GB/s of algorithmic bytes
@@ -142,24 +143,19 @@ def main():
     # steps only and a Reuse attend finds other layers' data in the caches, never its own.
     sel3 = Timed("select_reuse", lambda: d3.select(workspace=ws3s))
     att3 = Timed("attend_reuse", lambda: d3.attend(workspace=ws3a))
+    pack3 = Timed("pack_reuse", lambda: d3.pack())
+    attp3 = Timed("attend_packed_reuse", lambda: d3.attend_packed(workspace=ws3a))
     den4 = Timed("dense_refresh", lambda: d4.dense_refresh())
     sel5 = Timed("select_mixed", lambda: d5.select(workspace=ws5s))
     att5 = Timed("attend_mixed", lambda: d5.attend(workspace=ws5a))
-    calls = []
-    if args.only in ("all", "reuse"):
-        calls += [att3]
-    if args.only in ("all", "mixed"):
-        calls += [sel5]
-    if args.only in ("all", "refresh"):
-        calls += [den4]
-    if args.only in ("all", "reuse"):
-        calls += [sel3]
-    if args.only in ("all", "mixed"):
-        calls += [att5]
-    # the kept-row indices the first attend calls read
-    if args.only in ("all", "reuse"):
+    reuse, refresh, mixed = (args.only in ("all", w) for w in ("reuse", "refresh", "mixed"))
+    calls = [c for c, on in ((att3, reuse), (sel5, mixed), (pack3, reuse), (den4, refresh), (sel3, reuse),
+                             (attp3, reuse), (att5, mixed)) if on]
+    # the kept-row indices (and the packed cache) that the first attend calls read
+    if reuse:
         d3.select(workspace=ws3s)
-    if args.only in ("all", "mixed"):
+        d3.pack()
+    if mixed:
         d5.select(workspace=ws5s)
     torch.cuda.synchronize()
 
@@ -194,6 +190,8 @@ def main():
     select_gbps = rate_gbps(w3.select_bytes(), "select_reuse")
     refresh_tflops = rate_tflops(w4.attend_dense_flops(), "dense_refresh")
     mixed_sel_gbps = rate_gbps(w5.select_bytes(), "select_mixed")
+    pack_gbps = rate_gbps(w3.pack_bytes(), "pack_reuse")
+    packed_gbps = rate_gbps(w3.attend_packed_bytes(), "attend_packed_reuse")
 
     def roof(bound, achieved, peak, unit, kernel, algorithmic):
         if achieved is None:
@@ -234,6 +232,9 @@ def main():
         "refresh_tflops": refresh_tflops,
         "refresh_pct_of_mfma_peak": None if refresh_tflops is None else 100.0 * refresh_tflops / MFMA_BF16_PEAK_TFLOPS,
         "mixed_select_gbps": mixed_sel_gbps,
+        # the paper's layout (pack once at Refresh, then read the packed cache sequentially) beside the gather design
+        "reuse_pack_gbps": pack_gbps,
+        "reuse_attend_packed_gbps": packed_gbps,
         "call_ms_mean_min": {k: [round(v[0], 5), round(v[1], 5)] for k, v in T.items()},
         # the kernel that dominates the step's time is the dense Refresh kernel (one launch per call)
         "roofline": roof("mfma", refresh_tflops, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "attend_dense_bf16_kernel",

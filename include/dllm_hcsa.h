@@ -13,7 +13,9 @@
  *                              flagged dense attending over all their rows in the same call (the
  *                              mixed Refresh + Reuse batch of Section 5.3);
  *   dllm_dense_refresh_attend  dense bidirectional attention, all queries against all keys
- *                              (Refresh phase, Section 2.3 Eq. 3).
+ *                              (Refresh phase, Section 2.3 Eq. 3);
+ *   dllm_hcsa_pack             gather-copy of each head's kept rows into a dense per-request buffer
+ *                              (Section 4.5, the packing done at Refresh time).
  *
  * K and V stay in their dense layout; kept rows are fetched through the index lists at attention time.
  *
@@ -116,7 +118,9 @@ dllm_status dllm_hcsa_select(const dllm_batch *batch,
  * (k_b == 0 sparse, or L_b == 0 dense) gets zeros.  Scores, softmax state and accumulators are
  * fp32; bf16 inputs are multiplied on the matrix cores, fp32 inputs with fp32 arithmetic.
  *
- * seq_mode may be NULL (all sparse).  idx and cu_k may be NULL only if total_k == 0.
+ * seq_mode may be NULL (all sparse).  cu_k may be NULL only if total_k == 0.  idx == NULL with
+ * total_k > 0 means the identity lists: sparse sequence b attends over its rows 0 .. k_b-1 in order
+ * (k_b from cu_k), which is how a packed cache written by dllm_hcsa_pack is read.
  * max_k bounds k_b over sparse sequences (0 allowed when there are none).
  */
 size_t dllm_hcsa_attend_workspace(const dllm_batch *batch, int32_t max_k);
@@ -127,6 +131,27 @@ dllm_status dllm_hcsa_attend(const dllm_batch *batch,
                              const uint8_t *seq_mode, /* device, [batch] or NULL */
                              void *o,             /* device, [total_q, n_q_heads, head_dim] */
                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Pack (Section 4.5, "Decoupling Logical Sparsity from Physical Layout"): copies every head's kept
+ * rows, in list order, out of the dense K and V into two buffers of shape
+ * [n_q_heads, total_k, head_dim] (same element type), so that a later Reuse step reads them
+ * sequentially and needs no index list:
+ *     k_packed[h, cu_k[b] + t, :] = K[cu_kv[b] + idx[h, cu_k[b] + t], h / G, :]      (same for V)
+ * The packed buffers are themselves a valid K/V operand of this library: describe them in a
+ * dllm_batch with n_kv_heads = n_q_heads, kv_stride_tok = head_dim, kv_stride_head =
+ * total_k * head_dim, cu_kv = cu_k, total_kv = total_k, max_kv = max_k, and call dllm_hcsa_attend
+ * with idx = NULL (see there): that is the paper's Reuse phase over the packed cache.
+ * Needs no workspace.  idx, cu_k, k_packed and v_packed are device pointers; k_packed and v_packed
+ * must be 16-byte aligned and must not overlap K or V.
+ */
+dllm_status dllm_hcsa_pack(const dllm_batch *batch,
+                           const int32_t *idx,  /* device, [n_q_heads, total_k] */
+                           const int32_t *cu_k, /* device, [batch+1] */
+                           int32_t total_k, int32_t max_k,
+                           void *k_packed,      /* device, [n_q_heads, total_k, head_dim] */
+                           void *v_packed,      /* device, [n_q_heads, total_k, head_dim] */
+                           void *hip_stream);
 
 /*
  * Dense bidirectional attention of every sequence's queries over all of its keys

@@ -148,3 +148,25 @@ def attend(q, k, v, cu_q, cu_kv, idx, cu_k, seq_mode, softmax_scale: float):
                                _p(idx), _p(cu_k), _p(seq_mode), float(softmax_scale), _p(out))
     _check(rc, "oracle_attend")
     return out
+
+
+def pack(k, v, cu_kv, idx, cu_k):
+    """Section 4.5 packing by its definition: for every query head h, sequence b and list position
+    t, packed[h, cu_k[b] + t, :] = X[cu_kv[b] + idx[h, cu_k[b] + t], h // G, :] for X = K and V.
+    Plain Python loops over (head, sequence); elements keep their type (fp32, or bf16 bit patterns)."""
+    k, v = _c(k), _c(v)
+    cu_kv, cu_k, idx = _c(cu_kv, np.int32), _c(cu_k, np.int32), _c(idx, np.int32)
+    assert k.ndim == 3 and v.shape == k.shape and idx.ndim == 2 and idx.shape[1] == cu_k[-1]
+    Hq, Hkv, D = idx.shape[0], k.shape[1], k.shape[2]
+    assert Hq % Hkv == 0
+    G = Hq // Hkv
+    kp = np.zeros((Hq, int(cu_k[-1]), D), dtype=k.dtype)
+    vp = np.zeros((Hq, int(cu_k[-1]), D), dtype=v.dtype)
+    for h in range(Hq):
+        for b in range(len(cu_k) - 1):
+            for t in range(int(cu_k[b]), int(cu_k[b + 1])):
+                row = int(cu_kv[b]) + int(idx[h, t])
+                assert int(cu_kv[b]) <= row < int(cu_kv[b + 1])
+                kp[h, t, :] = k[row, h // G, :]
+                vp[h, t, :] = v[row, h // G, :]
+    return kp, vp

@@ -196,7 +196,6 @@ dllm_status dllm_hcsa_attend(const dllm_batch* batch, const int32_t* idx, const 
                 max_k, total_k, batch->max_kv);
   if (cu_k == nullptr && (total_k > 0 || seq_mode == nullptr))
     return fail(DLLM_ERR_INVALID_ARG, "cu_k may be NULL only when every sequence is flagged dense");
-  if (idx == nullptr && total_k > 0) return fail(DLLM_ERR_INVALID_ARG, "idx is NULL but total_k is %d", total_k);
   if (seq_mode != nullptr && (st = check_dense_strides(batch)) != DLLM_OK) return st;
   if (total_k > 0 && (st = check_sparse_strides(batch)) != DLLM_OK) return st;
   const dllm::AttendPlan plan = dllm::plan_attend(s, batch->dtype, max_k);
@@ -221,6 +220,24 @@ dllm_status dllm_hcsa_attend(const dllm_batch* batch, const int32_t* idx, const 
                                           total_k, seq_mode, o, workspace, stream);
   }
   return device_result(e, "dllm_hcsa_attend");
+}
+
+dllm_status dllm_hcsa_pack(const dllm_batch* batch, const int32_t* idx, const int32_t* cu_k, int32_t total_k,
+                           int32_t max_k, void* k_packed, void* v_packed, void* hip_stream) {
+  dllm::Shape s;
+  dllm_status st = check_batch(batch, &s);
+  if (st != DLLM_OK) return st;
+  if (idx == nullptr || cu_k == nullptr || k_packed == nullptr || v_packed == nullptr)
+    return fail(DLLM_ERR_INVALID_ARG, "idx, cu_k, k_packed and v_packed must be non-NULL");
+  if (!aligned16(k_packed) || !aligned16(v_packed))
+    return fail(DLLM_ERR_INVALID_ARG, "k_packed and v_packed must be 16-byte aligned");
+  if (total_k < 1 || max_k < 1 || max_k > total_k || max_k > batch->max_kv)
+    return fail(DLLM_ERR_INVALID_ARG, "need 1 <= max_k <= min(total_k, max_kv) (got max_k=%d, total_k=%d, max_kv=%d)",
+                max_k, total_k, batch->max_kv);
+  g_err[0] = 0;
+  return device_result(dllm::launch_pack(s, batch->dtype, batch->k, batch->v, batch->cu_kv, idx, cu_k, total_k, max_k,
+                                         k_packed, v_packed, static_cast<hipStream_t>(hip_stream)),
+                       "dllm_hcsa_pack");
 }
 
 size_t dllm_dense_refresh_attend_workspace(const dllm_batch* batch) {

@@ -30,15 +30,6 @@
 
 #include "attn_tile.h"
 
-#ifdef DLLM_TIMING
-__device__ unsigned long long g_dense_dbg[8192 * 8];
-extern "C" int dllm_debug_fetch(void* dst, size_t nbytes) {
-  return int(hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_dense_dbg), nbytes < sizeof(g_dense_dbg) ? nbytes : sizeof(g_dense_dbg)));
-}
-#define DBG_T(slot) if (threadIdx.x == 0) g_dense_dbg[dbg_wg * 8 + slot] = wall_clock64()
-#else
-#define DBG_T(slot)
-#endif
 
 namespace dllm {
 
@@ -74,10 +65,6 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   // times, while consecutive (sequence, head) pairs still go to different XCDs.
   const int nx = gridDim.x, groups = gridDim.y * gridDim.z;
   const int n = blockIdx.x + nx * (blockIdx.y + gridDim.y * blockIdx.z);
-#ifdef DLLM_TIMING
-  const int dbg_wg = n < 8192 ? n : 8191;
-  DBG_T(0);
-#endif
   int qtile = blockIdx.x, gi = blockIdx.y + gridDim.y * blockIdx.z;
   if ((groups & 7) == 0) {
     const int j = n >> 3;   // position in this XCD's own launch sequence
@@ -194,11 +181,7 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   // A operands of one step's score chain: rows = 32 keys at byte offset `koff` of the K ring
   auto k_operands = [&](v4u (&kop)[NT], int koff) {
 #pragma unroll
-#ifdef DLLM_ABL_NOLDSREAD
-    for (int t = 0; t < NT; ++t) kop[t] = qreg[0][(t + 1) % NT];
-#else
     for (int t = 0; t < NT; ++t) kop[t] = *reinterpret_cast<const v4u*>(smem + ka[t] + koff);
-#endif
   };
   // scores of a 32-key step relative to the running maxima: rows = keys, columns = this wave's queries
   auto score_chain = [&](f32x16 (&st)[NQB], const v4u (&kop)[NT]) {
@@ -251,12 +234,8 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       uint32_t w[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-#ifdef DLLM_ABL_NOEXP
-        const float p0 = st[qb][8 * u + 2 * j], p1 = st[qb][8 * u + 2 * j + 1];
-#else
         const float p0 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j]);
         const float p1 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j + 1]);
-#endif
         w[j] = cvt_pk_bf16(p0, p1);
         lsum[qb] = add_pair_bf16(w[j], lsum[qb]);
       }
@@ -267,13 +246,9 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   auto v_operands = [&](v4u (&vop)[NDB], int voff) {
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
-#ifdef DLLM_ABL_NOLDSREAD
-      vop[db] = qreg[0][db];
-#else
       const v2u lo = lds_read_tr16(smem + va[0][db] + voff);
       const v2u hi = lds_read_tr16(smem + va[1][db] + voff);
       vop[db] = v4u{lo.x, lo.y, hi.x, hi.y};
-#endif
     }
   };
   auto accumulate = [&](const v4u (&vop)[NDB], const v4u (&pb)[NQB]) {
@@ -307,11 +282,6 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   // One 32-key step.  R is its position in the common turn of the rings, which fixes every LDS
   // offset.  The step multiplies P of step i with V tile (R/2) % 2, half R%2, computes the scores of
   // step i+1 from K operands fetched during step i-1, and fetches those of step i+2.
-  DBG_T(1);
-#ifdef DLLM_TIMING
-  unsigned long long dbg_vm = 0, dbg_bar = 0;
-  if (threadIdx.x == 0) g_dense_dbg[dbg_wg * 8 + 4] = __builtin_readcyclecounter();
-#endif
   int i = 0;
   auto step = [&](auto rc, f32x16 (&cur)[NQB], f32x16 (&nxt)[NQB]) {
     constexpr int R = decltype(rc)::value;
@@ -321,23 +291,10 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     if (kb == 0) {
       // Tile boundary: everyone is done with tile-1, and the loads issued a tile ago (K of tile+1,
       // V of this tile) have landed.  The slots of tile-1 take K of tile+2 and V of tile+1.
-#ifdef DLLM_TIMING
-      const unsigned long long tw0 = wall_clock64();
-      wait_tile_loads();
-      const unsigned long long tw1 = wall_clock64();
-      __syncthreads();
-      const unsigned long long tw2 = wall_clock64();
-      dbg_vm += tw1 - tw0;
-      dbg_bar += tw2 - tw1;
-#elif defined(DLLM_ABL_NOSYNC)
-#else
       wait_tile_loads();
       __syncthreads();
-#endif
-#ifndef DLLM_ABL_NOLOAD
       if (tile + 2 < ntiles) load_tile(kbase, tile + 2, ((T + 2) % kDenseRingK) * TILEB);
       if (tile + 1 < ntiles) load_tile(vbase, tile + 1, VBASE + ((T + 1) % kDenseRingV) * TILEB);
-#endif
     }
     constexpr int voff = (T % kDenseRingV) * TILEB + kb * 32 * ROWB;
     v4u pb0[NQB], pb1[NQB], vop0[NDB], vop1[NDB];
@@ -425,12 +382,6 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     if (i >= nsteps) break;
     step(std::integral_constant<int, 11>{}, st_b, st_a);
   }
-
-  DBG_T(2);
-#ifdef DLLM_TIMING
-  if (threadIdx.x == 0) g_dense_dbg[dbg_wg * 8 + 5] = __builtin_readcyclecounter();
-  if (threadIdx.x == 0) { g_dense_dbg[dbg_wg * 8 + 6] = dbg_vm; g_dense_dbg[dbg_wg * 8 + 7] = dbg_bar; }
-#endif
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int qi = qbase + (wave * NQB + qb) * 32 + col;
@@ -450,7 +401,6 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       }
     }
   }
-  DBG_T(3);
 }
 
 // Four waves per workgroup, one 32-query block each; two workgroups per compute unit (two waves per SIMD).

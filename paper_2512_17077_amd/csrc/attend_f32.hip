@@ -40,7 +40,9 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(
   const int o0 = dense ? 0 : cu_k[b];
   const int n = dense ? L : cu_k[b + 1] - o0;
   const int g = h / s.group;
-  const int32_t* __restrict__ rows = dense ? nullptr : idx + int64_t(h) * total_k + o0;
+  // a NULL idx stands for the identity lists (kept rows 0 .. k_b-1): then a row is its own list position
+  const bool direct = dense || idx == nullptr;
+  const int32_t* __restrict__ rows = direct ? nullptr : idx + int64_t(h) * total_k + o0;
 
   float qr[D];
   const float* qp = q + int64_t(q0 + i) * s.q_tok + int64_t(h) * s.q_head;
@@ -60,7 +62,7 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(
   for (int t0 = 0; t0 < n; t0 += 64) {
     const int t = t0 + lane;
     const bool ok = t < n;
-    const int r = ok ? (dense ? t : rows[t]) : 0;
+    const int r = ok ? (direct ? t : rows[t]) : 0;
     float z = -INFINITY;
     if (ok) {
       const float* kr = kb + int64_t(r) * s.kv_tok;

@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
     for (int j = 0; j < kMaxTilesPerWave / 2; ++j) {
       const int slot = j * 64 + lane;   // tile slot / 32, row slot % 32 of this wave
       const int t = min(c0 + (wave + (slot >> 5) * kWaves) * kTile + (slot & 31), c1 - 1);
-      my_rows[slot] = rows[t];
+      my_rows[slot] = idx != nullptr ? rows[t] : t;   // NULL idx: identity lists (a packed cache)
     }
     __syncthreads();   // Q tile and row ids are in place
     // gather the wave's j-th tile into a register buffer

@@ -33,6 +33,11 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
                          const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t max_k,
                          int32_t pool_w, int32_t* idx_out, void* ws, hipStream_t st);
 
+// ---- packing of the kept rows (pack_kernels.hip)
+hipError_t launch_pack(const Shape& s, dllm_dtype dt, const void* k, const void* v, const int32_t* cu_kv,
+                       const int32_t* idx, const int32_t* cu_k, int32_t total_k, int32_t max_k, void* kp, void* vp,
+                       hipStream_t st);
+
 // ---- attention over kept rows / all rows (attend_*.hip)
 struct AttendPlan {
   int32_t chunk_rows;  // kept rows one workgroup walks

@@ -28,6 +28,7 @@ EXPORTS = [
     "dllm_hcsa_select_workspace", "dllm_hcsa_select",
     "dllm_hcsa_attend_workspace", "dllm_hcsa_attend",
     "dllm_dense_refresh_attend_workspace", "dllm_dense_refresh_attend",
+    "dllm_hcsa_pack",
     "dllm_last_error", "dllm_hcsa_version",
 ]
 
@@ -88,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.dllm_dense_refresh_attend_workspace.argtypes = [P]
         L.dllm_dense_refresh_attend.restype = ctypes.c_int
         L.dllm_dense_refresh_attend.argtypes = [P, vp, vp, sz, vp]
+        L.dllm_hcsa_pack.restype = ctypes.c_int
+        L.dllm_hcsa_pack.argtypes = [P, vp, vp, i32, i32, vp, vp, vp]
         L.dllm_last_error.restype = ctypes.c_char_p
         L.dllm_last_error.argtypes = []
         L.dllm_hcsa_version.restype = i32
@@ -186,6 +189,22 @@ def dllm_dense_refresh_attend(batch: DllmBatch, o: torch.Tensor, workspace: Opti
     return o
 
 
+def dllm_hcsa_pack(batch: DllmBatch, idx: torch.Tensor, cu_k: torch.Tensor, total_k: int, max_k: int,
+                   k_packed: torch.Tensor, v_packed: torch.Tensor, stream=None):
+    """Copy every head's kept rows into k_packed / v_packed [Hq, total_k, D]."""
+    _raise(lib().dllm_hcsa_pack(ctypes.byref(batch), _ptr(idx), _ptr(cu_k), int(total_k), int(max_k),
+                                _ptr(k_packed), _ptr(v_packed), _stream(stream)))
+    return k_packed, v_packed
+
+
+def make_packed_batch(q: torch.Tensor, k_packed: torch.Tensor, v_packed: torch.Tensor, cu_q: torch.Tensor,
+                      cu_k: torch.Tensor, max_q: int, max_k: int, softmax_scale: float) -> DllmBatch:
+    """Describe packed buffers [Hq, total_k, D] as the K/V operand of an attend call: one KV head per
+    query head, rows of a head contiguous, sequence b owning list positions cu_k[b] .. cu_k[b+1]-1."""
+    assert k_packed.dim() == 3 and k_packed.is_contiguous() and v_packed.is_contiguous()
+    return make_batch(q, k_packed.transpose(0, 1), v_packed.transpose(0, 1), cu_q, cu_k, max_q, max_k, softmax_scale)
+
+
 class DeviceWorkload:
     """A synth.Workload copied to the GPU, with the library's descriptor ready."""
 
@@ -218,3 +237,18 @@ class DeviceWorkload:
 
     def dense_refresh(self):
         return dllm_dense_refresh_attend(self.batch, self.o)
+
+    def pack(self, idx=None):
+        """Pack the kept rows (allocates the packed buffers and their batch descriptor once)."""
+        if not hasattr(self, "k_packed"):
+            shape = (self.w.n_q_heads, self.total_k, self.w.head_dim)
+            self.k_packed = torch.empty(shape, dtype=self.q.dtype, device=self.device)
+            self.v_packed = torch.empty(shape, dtype=self.q.dtype, device=self.device)
+            self.packed_batch = make_packed_batch(self.q, self.k_packed, self.v_packed, self.cu_q, self.cu_k,
+                                                  self.max_q, self.max_k, self.w.softmax_scale)
+        return dllm_hcsa_pack(self.batch, self.idx if idx is None else idx, self.cu_k, self.total_k, self.max_k,
+                              self.k_packed, self.v_packed)
+
+    def attend_packed(self, workspace=None):
+        """Reuse attention over the packed cache: identity lists (idx = NULL) on the packed batch."""
+        return dllm_hcsa_attend(self.packed_batch, None, self.cu_k, self.total_k, self.max_k, None, self.o, workspace)

@@ -100,6 +100,19 @@ class Workload:
         nk = int(self.keep[sp].sum())
         return 2 * nk * self.n_q_heads * d * e + 2 * nq * self.n_q_heads * d * e + nk * self.n_q_heads * 4
 
+    def pack_bytes(self) -> int:
+        """Algorithmic bytes of packing: every kept (query head, position) pair reads one K row and
+        one V row and writes them again, plus the indices read."""
+        e, d = self.elem_bytes, self.head_dim
+        sp = self.seq_mode == MODE_SPARSE
+        nk = int(self.keep[sp].sum())
+        return 4 * nk * self.n_q_heads * d * e + nk * self.n_q_heads * 4
+
+    def attend_packed_bytes(self) -> int:
+        """Algorithmic bytes of Reuse attention over a packed cache: as attend_sparse_bytes, without indices."""
+        sp = self.seq_mode == MODE_SPARSE
+        return self.attend_sparse_bytes() - int(self.keep[sp].sum()) * self.n_q_heads * 4
+
     def attend_dense_flops(self) -> int:
         """4 * Lq * Lkv * D per (sequence, query head) for dense sequences."""
         dn = self.seq_mode == MODE_DENSE

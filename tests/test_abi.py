@@ -93,7 +93,6 @@ def test_attend_scalar_checks():
     assert attend_status(b, o=None) == hcsa.DLLM_ERR_INVALID_ARG
     assert attend_status(b, max_k=-1) == hcsa.DLLM_ERR_INVALID_ARG
     assert attend_status(b, max_k=301, total_k=400) == hcsa.DLLM_ERR_INVALID_ARG
-    assert attend_status(b, idx=None) == hcsa.DLLM_ERR_INVALID_ARG
     assert attend_status(b, cu_k=None) == hcsa.DLLM_ERR_INVALID_ARG
     assert attend_status(b, o=ctypes.c_void_p(0x30004)) == hcsa.DLLM_ERR_INVALID_ARG
     assert hcsa.lib().dllm_dense_refresh_attend(ctypes.byref(b), None, None, 0, None) == hcsa.DLLM_ERR_INVALID_ARG
@@ -103,6 +102,23 @@ def test_attend_scalar_checks():
     assert need > 0
     assert attend_status(b, total_k=4000, max_k=4000, ws=None) == hcsa.DLLM_ERR_WORKSPACE
     assert attend_status(b, total_k=4000, max_k=4000, ws_bytes=need - 1) == hcsa.DLLM_ERR_WORKSPACE
+
+
+def test_pack_argument_checks():
+    b = good_batch()
+    L = hcsa.lib()
+
+    def pack_status(idx=FAKE, cu_k=FAKE, total_k=100, max_k=50, kp=FAKE, vp=FAKE):
+        return L.dllm_hcsa_pack(ctypes.byref(b), idx, cu_k, total_k, max_k, kp, vp, None)
+
+    assert pack_status(idx=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert pack_status(cu_k=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert pack_status(kp=None) == hcsa.DLLM_ERR_INVALID_ARG
+    assert pack_status(vp=ctypes.c_void_p(0x30004)) == hcsa.DLLM_ERR_INVALID_ARG
+    assert pack_status(total_k=0) == hcsa.DLLM_ERR_INVALID_ARG
+    assert pack_status(max_k=0) == hcsa.DLLM_ERR_INVALID_ARG
+    assert pack_status(max_k=101) == hcsa.DLLM_ERR_INVALID_ARG
+    assert "max_k" in hcsa.last_error()
 
 
 def test_python_struct_matches_the_header_layout(tmp_path):

@@ -271,3 +271,43 @@ def test_mixed_config5_full_size():
     want = oracle_attend(sub, ref)
     got = dw.o[torch.from_numpy(rows).cuda()].float().cpu().numpy()
     assert np.abs(got - want).max() <= 2e-2
+
+
+# ------------------------------------------------------------------ packing (Section 4.5) and the packed Reuse step
+
+def check_pack_and_packed_attend(w, name):
+    say(f"pack {name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
+        f"maxk={int(w.keep.max())}")
+    idx = oracle_select(w)
+    dw = hcsa.DeviceWorkload(w)
+    dw.idx.copy_(torch.from_numpy(idx))
+    dw.pack()
+    dw.k_packed.fill_(0)
+    dw.v_packed.fill_(0)
+    dw.pack()
+    torch.cuda.synchronize()
+    kp, vp = oracle.pack(synth.to_bits(w.k), synth.to_bits(w.v), w.cu_kv, idx, w.cu_k)
+    assert np.array_equal(synth.to_bits(dw.k_packed.cpu()), kp), "packed K differs from the oracle"
+    assert np.array_equal(synth.to_bits(dw.v_packed.cpu()), vp), "packed V differs from the oracle"
+    # Reuse step over the packed cache against the oracle's attention over the kept rows in place
+    dw.o.fill_(float("nan"))
+    dw.attend_packed()
+    torch.cuda.synchronize()
+    got = dw.o.float().cpu().numpy().astype(np.float64)
+    ref = oracle_attend(w, idx)
+    err = np.abs(got - ref)
+    assert np.isfinite(got).all(), "non-finite output"
+    assert err.max() <= TOL[w.dtype], f"max abs error {err.max():.3e}"
+
+
+@pytest.mark.parametrize("dtype,D,Hq,Hkv", [(torch.bfloat16, 128, 8, 8), (torch.bfloat16, 64, 8, 2),
+                                            (torch.float32, 64, 4, 4), (torch.float32, 128, 4, 2)])
+def test_pack_and_packed_attend_ragged(dtype, D, Hq, Hkv):
+    lens = [300, 65, 1, 777, 129]
+    keep = [37, 65, 1, 500, 128]
+    check_pack_and_packed_attend(custom(61, dtype, Hq, Hkv, D, lens, [32, 5, 1, 40, 32], keep, salient=0.05),
+                                 f"ragged {dtype} D={D}")
+
+
+def test_pack_and_packed_attend_config3_full():
+    check_pack_and_packed_attend(synth.config(3), "c3 full size")

@@ -398,6 +398,32 @@ def test_batch_equals_its_sequences_run_alone():
         assert np.array_equal(ob, out[cq[b]:cq[b + 1]])
 
 
+def test_pack_then_dense_attention_equals_attention_over_kept_rows():
+    """Section 4.5: a Reuse step over the packed cache must be the same attention as over the kept
+    rows in place.  The oracle visits the rows in the same order either way, so the two agree bit for
+    bit; the packed buffer itself is also checked entry by entry against direct indexing."""
+    rng = np.random.default_rng(41)
+    B, Hq, Hkv, D = 3, 4, 2, 8
+    lens, qlens, keep = [9, 14, 5], [3, 2, 4], [4, 7, 5]
+    Q, K, V, cq, ckv = rand_case(41, B=B, Hq=Hq, Hkv=Hkv, D=D, lens=lens, qlens=qlens, dtype="bf16", scale=0.3)
+    ck = cu(keep)
+    idx = np.zeros((Hq, ck[-1]), np.int32)
+    for h in range(Hq):
+        for b in range(B):
+            idx[h, ck[b]:ck[b + 1]] = rng.permutation(lens[b])[:keep[b]]     # unsorted on purpose
+    kp, vp = oracle.pack(K, V, ckv, idx, ck)
+    assert kp.shape == (Hq, ck[-1], D) and kp.dtype == K.dtype
+    for h, b, t in [(0, 0, 0), (3, 1, 6), (2, 2, 4), (1, 1, 0)]:
+        row = ckv[b] + idx[h, ck[b] + t]
+        assert np.array_equal(kp[h, ck[b] + t], K[row, h // (Hq // Hkv)])
+        assert np.array_equal(vp[h, ck[b] + t], V[row, h // (Hq // Hkv)])
+    sparse = oracle.attend(Q, K, V, cq, ckv, idx, ck, None, 0.3)
+    # the packed buffers as a K/V operand: one KV head per query head, sequence b owns positions ck[b]..ck[b+1]
+    kt, vt = np.ascontiguousarray(kp.transpose(1, 0, 2)), np.ascontiguousarray(vp.transpose(1, 0, 2))
+    dense = oracle.attend(Q, kt, vt, cq, ck, None, None, np.ones(B, np.uint8), 0.3)
+    assert np.array_equal(sparse, dense)
+
+
 def test_oracle_rejects_bad_arguments():
     q, k, v, cq, ckv = rand_case(14, lens=(16,), qlens=(4,))
     with pytest.raises(ValueError):
