@@ -49,6 +49,8 @@ def _load():
         lib.oracle_topk.argtypes = [i, i, vp, ip, ip, vp]
         lib.oracle_select.restype = i
         lib.oracle_select.argtypes = [i, i, i, i, i, vp, vp, ip, ip, ip, i, vp]
+        lib.oracle_select_ex.restype = i
+        lib.oracle_select_ex.argtypes = [i, i, i, i, i, vp, vp, ip, ip, ip, i, i, i, vp]
         lib.oracle_attend.restype = i
         lib.oracle_attend.argtypes = [i, i, i, i, i, vp, vp, vp, ip, ip, vp, ip, vp, ctypes.c_double, vp]
         _lib = lib
@@ -123,6 +125,20 @@ def select(q, k, cu_q, cu_kv, cu_k, pool_w: int = 1):
     rc = _load().oracle_select(_dtype_code(q), B, Hq, Hkv, D, _p(q), _p(k), _p(cu_q), _p(cu_kv),
                                _p(cu_k), int(pool_w), _p(idx))
     _check(rc, "oracle_select")
+    return idx
+
+
+def select_ex(q, k, cu_q, cu_kv, cu_k, pool_w: int = 1, forced_tail: int = 0, head_sum: bool = False):
+    """Selection with the active block's own positions (the last `forced_tail` of every sequence)
+    always kept (Eq. 4), and / or with one list shared by all heads from head-summed scores (Eq. 5)."""
+    q, k = _c(q), _c(k)
+    cu_q, cu_kv, cu_k = _c(cu_q, np.int32), _c(cu_kv, np.int32), _c(cu_k, np.int32)
+    B, Hq, Hkv, D = _dims(q, k, cu_q, cu_kv)
+    assert _dtype_code(q) == _dtype_code(k)
+    idx = np.empty((Hq, int(cu_k[-1])), dtype=np.int32)
+    rc = _load().oracle_select_ex(_dtype_code(q), B, Hq, Hkv, D, _p(q), _p(k), _p(cu_q), _p(cu_kv), _p(cu_k),
+                                  int(pool_w), int(forced_tail), int(bool(head_sum)), _p(idx))
+    _check(rc, "oracle_select_ex")
     return idx
 
 

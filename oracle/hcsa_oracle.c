@@ -221,6 +221,84 @@ int oracle_select(int dtype, int B, int Hq, int Hkv, int D,
     return rc;
 }
 
+/* Selection variants.
+ *
+ * forced_tail = n > 0: Section 2.3 Eq. (4) attends over [K_b; K_cache], the active block's own keys
+ * and values beside the cache.  With the block stored as the last n positions of the sequence, those
+ * n positions are always kept and never ranked; the k_b - n best of the candidates 0 .. L_b-n-1 are
+ * chosen as usual (the pooling window is clipped to the candidates) and the n block positions are
+ * appended, so the list stays ascending.
+ *
+ * head_sum != 0: the shared selection of Section 2.4 Eq. (5): the pooled per-head scores are summed
+ * over the query heads (fp32, ascending head, starting from +0), one TopK per sequence is taken, and
+ * every head gets the same list.
+ */
+int oracle_select_ex(int dtype, int B, int Hq, int Hkv, int D,
+                     const void *q, const void *k,
+                     const int32_t *cu_q, const int32_t *cu_kv, const int32_t *cu_k,
+                     int pool_w, int forced_tail, int head_sum, int32_t *idx_out)
+{
+    int rc = check_common(dtype, B, Hq, Hkv, D, cu_q, cu_kv);
+    if (rc) return rc;
+    if (pool_w < 1 || pool_w % 2 == 0 || forced_tail < 0 || !cu_k || !idx_out) return ORACLE_BAD_ARG;
+    if (cu_k[0] != 0) return ORACLE_BAD_ARG;
+    for (int b = 0; b < B; ++b) {
+        const int64_t L = cu_kv[b + 1] - cu_kv[b], kb = cu_k[b + 1] - cu_k[b];
+        if (kb < 0 || kb > L) return ORACLE_BAD_ARG;
+        if (kb > 0 && (kb < forced_tail || L < forced_tail)) return ORACLE_BAD_ARG;
+    }
+    const int64_t total_kv = cu_kv[B], total_k = cu_k[B];
+    const int half = pool_w / 2;
+    float *raw = (float *)malloc(sizeof(float) * (size_t)(total_kv > 0 ? total_kv : 1) * (size_t)Hq);
+    if (!raw) return ORACLE_NO_MEM;
+    rc = oracle_score(dtype, B, Hq, Hkv, D, q, k, cu_q, cu_kv, 1, raw, NULL);   /* unpooled Eq. (6) scores */
+    if (rc) { free(raw); return rc; }
+
+    for (int b = 0; b < B; ++b) {
+        const int64_t k0 = cu_kv[b], L = cu_kv[b + 1] - cu_kv[b];
+        const int64_t o0 = cu_k[b], kb = cu_k[b + 1] - cu_k[b];
+        if (kb == 0) continue;
+        const int64_t Lc = L - forced_tail, kc = kb - forced_tail;   /* candidates, and how many of them are kept */
+        float *pooled = (float *)malloc(sizeof(float) * (size_t)(Lc > 0 ? Lc : 1) * (size_t)Hq);
+        scored_pos *p = (scored_pos *)malloc(sizeof(scored_pos) * (size_t)(Lc > 0 ? Lc : 1));
+        if (!pooled || !p) { free(pooled); free(p); free(raw); return ORACLE_NO_MEM; }
+        for (int h = 0; h < Hq; ++h)
+            for (int64_t j = 0; j < Lc; ++j) {
+                int64_t lo = j - half < 0 ? 0 : j - half;
+                int64_t hi = j + half > Lc - 1 ? Lc - 1 : j + half;
+                float m = raw[(int64_t)h * total_kv + k0 + lo];
+                for (int64_t t = lo + 1; t <= hi; ++t)
+                    if (raw[(int64_t)h * total_kv + k0 + t] > m) m = raw[(int64_t)h * total_kv + k0 + t];
+                pooled[(int64_t)h * Lc + j] = m;
+            }
+        const int lists = head_sum ? 1 : Hq;
+        for (int li = 0; li < lists; ++li) {
+            for (int64_t j = 0; j < Lc; ++j) {
+                float sc;
+                if (head_sum) {
+                    sc = 0.0f;
+                    for (int h = 0; h < Hq; ++h) sc = sc + pooled[(int64_t)h * Lc + j];
+                } else {
+                    sc = pooled[(int64_t)li * Lc + j];
+                }
+                p[j].s = sc;
+                p[j].j = (int32_t)j;
+            }
+            qsort(p, (size_t)Lc, sizeof(scored_pos), by_score_then_pos);
+            qsort(p, (size_t)kc, sizeof(scored_pos), by_pos);
+            for (int h = head_sum ? 0 : li; h < (head_sum ? Hq : li + 1); ++h) {
+                for (int64_t t = 0; t < kc; ++t) idx_out[(int64_t)h * total_k + o0 + t] = p[t].j;
+                for (int64_t t = 0; t < forced_tail; ++t)
+                    idx_out[(int64_t)h * total_k + o0 + kc + t] = (int32_t)(Lc + t);
+            }
+        }
+        free(pooled); free(p);
+    }
+    free(raw);
+    return ORACLE_OK;
+}
+
+
 /* Eq. (4) over each head's kept rows (seq_mode[b] == 0, rows idx[h, cu_k[b] .. cu_k[b+1]))
  * and Eq. (3) over all rows (seq_mode[b] == 1); seq_mode NULL means all sparse.
  * o_out [total_q, Hq, D] in fp64. */

@@ -424,6 +424,66 @@ def test_pack_then_dense_attention_equals_attention_over_kept_rows():
     assert np.array_equal(sparse, dense)
 
 
+# --------------------------------------------------------------------------- selection variants
+
+def _drop_tail(K, ckv, n):
+    """K without the last n rows of every sequence, and the matching offsets."""
+    lens = np.diff(ckv)
+    keep = np.concatenate([np.arange(ckv[b], ckv[b + 1] - n) for b in range(len(lens))])
+    return np.ascontiguousarray(K[keep]), cu(lens - n)
+
+
+@pytest.mark.parametrize("pool_w", [1, 3])
+def test_select_variants_reduce_to_the_plain_selection(pool_w):
+    Q, K, V, cq, ckv = rand_case(51, B=3, Hq=4, Hkv=2, D=8, lens=[40, 17, 64], qlens=[4, 2, 8], dtype="bf16")
+    ck = cu([10, 17, 9])
+    plain = oracle.select(Q, K, cq, ckv, ck, pool_w)
+    assert np.array_equal(oracle.select_ex(Q, K, cq, ckv, ck, pool_w, 0, False), plain)
+
+
+@pytest.mark.parametrize("pool_w", [1, 3])
+def test_forced_tail_is_plain_selection_on_the_context_plus_the_block(pool_w):
+    """Eq. (4): the block's own positions (the last n) are always attended; the cache part is the plain
+    TopK over the context alone, so it must equal the pinned selection run on the sequences with their
+    last n rows removed."""
+    n = 4
+    lens, keep = [40, 17, 64], [10, 17, 9]
+    Q, K, V, cq, ckv = rand_case(52, B=3, Hq=4, Hkv=2, D=8, lens=lens, qlens=[4, 4, 4], dtype="f32")
+    ck = cu(keep)
+    got = oracle.select_ex(Q, K, cq, ckv, ck, pool_w, n, False)
+    Kc, ckv_c = _drop_tail(K, ckv, n)
+    ctx = oracle.select(Q, Kc, cq, ckv_c, cu([k - n for k in keep]), pool_w)
+    for b in range(3):
+        for h in range(4):
+            mine = got[h, ck[b]:ck[b + 1]]
+            assert np.array_equal(mine[:keep[b] - n], ctx[h, ck[b] - n * b:ck[b + 1] - n * (b + 1)])
+            assert np.array_equal(mine[keep[b] - n:], np.arange(lens[b] - n, lens[b]))
+            assert np.all(np.diff(mine) > 0)
+    with pytest.raises(ValueError):
+        oracle.select_ex(Q, K, cq, ckv, cu([10, 3, 9]), pool_w, n, False)    # fewer kept rows than forced ones
+
+
+@pytest.mark.parametrize("pool_w", [1, 3])
+def test_head_summed_selection_against_brute_force(pool_w):
+    """Eq. (5): pooled per-head scores summed over heads (fp32, ascending head), one TopK, every head
+    gets the same list."""
+    lens, keep = [23, 9], [7, 9]
+    Q, K, V, cq, ckv = rand_case(53, B=2, Hq=4, Hkv=2, D=8, lens=lens, qlens=[3, 5], dtype="bf16")
+    ck = cu(keep)
+    got = oracle.select_ex(Q, K, cq, ckv, ck, pool_w, 0, True)
+    s = oracle.score(Q, K, cq, ckv, pool_w)                 # pinned per-head pooled scores
+    for b in range(2):
+        tot = np.zeros(lens[b], np.float32)
+        for h in range(4):
+            tot = (tot + s[h, ckv[b]:ckv[b + 1]]).astype(np.float32)
+        want = brute_topk(tot, keep[b])
+        for h in range(4):
+            assert np.array_equal(got[h, ck[b]:ck[b + 1]], want)
+    # one head: summing changes nothing
+    Q1, K1 = Q[:, :1].copy(), K[:, :1].copy()
+    assert np.array_equal(oracle.select_ex(Q1, K1, cq, ckv, ck, pool_w, 0, True), oracle.select(Q1, K1, cq, ckv, ck, pool_w))
+
+
 def test_oracle_rejects_bad_arguments():
     q, k, v, cq, ckv = rand_case(14, lens=(16,), qlens=(4,))
     with pytest.raises(ValueError):
