@@ -109,6 +109,27 @@ dllm_status dllm_hcsa_select(const dllm_batch *batch,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Selection with two options; dllm_hcsa_select is this call with forced_tail = 0 and head_sum = 0.
+ *
+ * forced_tail = n > 0   Section 2.3 Eq. 4 attends over [K_b; K_cache]: the active block's own keys
+ *     and values next to the cache.  With the block stored as the last n positions of every
+ *     sequence, those n positions are always kept and never ranked: the k_b - n best of positions
+ *     0 .. L_b-n-1 are chosen as above (the pooling window is clipped to these candidates) and the n
+ *     block positions close the ascending list.  Requires n <= k_b for every sequence with k_b > 0
+ *     (not checked on the device); n <= max_k is checked.
+ * head_sum = 1          The shared selection of Section 2.4 Eq. 5: the pooled scores are summed over
+ *     the query heads (fp32, ascending head, starting from +0), one TopK is taken per sequence under
+ *     the same order, and every head's row of idx_out receives that list.
+ * Workspace as for dllm_hcsa_select.
+ */
+dllm_status dllm_hcsa_select_ex(const dllm_batch *batch,
+                                const int32_t *cu_k, /* device, [batch+1] */
+                                int32_t total_k, int32_t max_k, int32_t pool_w,
+                                int32_t forced_tail, int32_t head_sum,
+                                int32_t *idx_out,    /* device, [n_q_heads, total_k] */
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Attention over kept rows (Section 2.3 Eq. 4 restricted to each head's kept set; Eq. 3 for
  * sequences flagged dense).  For sequence b, head h, query row i:
  *     O[i,h,:] = sum_t softmax_t(softmax_scale * Q[i,h,:].K[r_t, h/G, :]) * V[r_t, h/G, :]

@@ -159,9 +159,9 @@ size_t dllm_hcsa_select_workspace(const dllm_batch* batch, int32_t max_k) {
   return dllm::plan_select(s).bytes;
 }
 
-dllm_status dllm_hcsa_select(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
-                             int32_t pool_w, int32_t* idx_out, void* workspace, size_t workspace_bytes,
-                             void* hip_stream) {
+dllm_status dllm_hcsa_select_ex(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
+                                int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
   dllm::Shape s;
   dllm_status st = check_batch(batch, &s);
   if (st != DLLM_OK) return st;
@@ -169,12 +169,22 @@ dllm_status dllm_hcsa_select(const dllm_batch* batch, const int32_t* cu_k, int32
   if (cu_k == nullptr || idx_out == nullptr) return fail(DLLM_ERR_INVALID_ARG, "cu_k and idx_out must be non-NULL");
   if (total_k < 1 || max_k > total_k)
     return fail(DLLM_ERR_INVALID_ARG, "need 1 <= max_k <= total_k (got max_k=%d, total_k=%d)", max_k, total_k);
+  if (forced_tail < 0 || forced_tail > max_k)
+    return fail(DLLM_ERR_INVALID_ARG, "forced_tail %d outside 0..max_k (%d)", forced_tail, max_k);
+  if (head_sum != 0 && head_sum != 1) return fail(DLLM_ERR_INVALID_ARG, "head_sum must be 0 or 1 (got %d)", head_sum);
   if ((st = check_workspace(workspace, workspace_bytes, dllm::plan_select(s).bytes)) != DLLM_OK) return st;
   g_err[0] = 0;
   return device_result(dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k,
-                                           total_k, max_k, pool_w, idx_out, workspace,
+                                           total_k, max_k, pool_w, forced_tail, head_sum, idx_out, workspace,
                                            static_cast<hipStream_t>(hip_stream)),
                        "dllm_hcsa_select");
+}
+
+dllm_status dllm_hcsa_select(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
+                             int32_t pool_w, int32_t* idx_out, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  return dllm_hcsa_select_ex(batch, cu_k, total_k, max_k, pool_w, 0, 0, idx_out, workspace, workspace_bytes,
+                             hip_stream);
 }
 
 size_t dllm_hcsa_attend_workspace(const dllm_batch* batch, int32_t max_k) {

@@ -31,7 +31,8 @@ struct SelectPlan {
 SelectPlan plan_select(const Shape& s);
 hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,
                          const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t max_k,
-                         int32_t pool_w, int32_t* idx_out, void* ws, hipStream_t st);
+                         int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out, void* ws,
+                         hipStream_t st);
 
 // ---- packing of the kept rows (pack_kernels.hip)
 hipError_t launch_pack(const Shape& s, dllm_dtype dt, const void* k, const void* v, const int32_t* cu_kv,

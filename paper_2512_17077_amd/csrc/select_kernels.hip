@@ -144,35 +144,64 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
+// forced_tail: the last forced_tail positions of the sequence are kept without being ranked (the
+// active block's own rows, Section 2.3 Eq. 4); the other kept rows are chosen among the positions
+// before them.  head_sum: one list per sequence from the scores summed over the n_heads query heads
+// (Section 2.4 Eq. 5), written to every head; the grid then has one workgroup per sequence.
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k,
-    int32_t total_kv, int32_t total_k, int32_t pool_w, int32_t lpad, int32_t* __restrict__ idx_out) {
+    int32_t total_kv, int32_t total_k, int32_t pool_w, int32_t lpad, int32_t forced_tail, int32_t head_sum,
+    int32_t n_heads, int32_t* __restrict__ idx_out) {
   extern __shared__ uint32_t dyn[];
   __shared__ uint32_t hist[256];
   __shared__ uint32_t wave_tot[kTopkThreads / 64];
   __shared__ uint32_t sh_prefix, sh_k;
 
   const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const int o0 = cu_k[b], kb = cu_k[b + 1] - o0;
-  if (kb == 0) return;
-  const int kv0 = cu_kv[b], L = cu_kv[b + 1] - kv0;
-  const float* __restrict__ src = scores + int64_t(h) * total_kv + kv0;
+  const int o0 = cu_k[b], kb_all = cu_k[b + 1] - o0;
+  if (kb_all == 0) return;
+  const int kv0 = cu_kv[b];
+  const int L = cu_kv[b + 1] - kv0 - forced_tail;   // candidates: the positions before the forced ones
+  const int kb = kb_all - forced_tail;              // kept among the candidates
+  const int h_first = head_sum ? 0 : h, h_last = head_sum ? n_heads : h + 1;   // heads that receive this list
   uint32_t* keys = dyn;
 
-  if (pool_w == 1) {
-    for (int j = tid; j < L; j += kTopkThreads) keys[j] = order_key(src[j]);
-  } else {
-    float* raw = reinterpret_cast<float*>(dyn + lpad);
-    for (int j = tid; j < L; j += kTopkThreads) raw[j] = src[j];
-    __syncthreads();
-    const int half = pool_w >> 1;
+  // forced positions close the (ascending) list
+  for (int t = tid; t < forced_tail; t += kTopkThreads)
+    for (int hh = h_first; hh < h_last; ++hh) idx_out[int64_t(hh) * total_k + o0 + kb + t] = L + t;
+  if (kb <= 0) return;
+
+  // pooled score of every candidate -> order-preserving key.  A thread owns positions tid, tid + 512, ...
+  // through all of this, so the head sum needs no exchange; only the pooling window reads neighbours.
+  float* raw = reinterpret_cast<float*>(dyn + lpad);
+  float* accum = reinterpret_cast<float*>(keys);
+  const int half = pool_w >> 1;
+  for (int hh = h_first; hh < h_last; ++hh) {
+    const float* __restrict__ src = scores + int64_t(hh) * total_kv + kv0;
+    if (pool_w > 1) {
+      if (hh != h_first) __syncthreads();   // everyone is done with the previous head's raw scores
+      for (int j = tid; j < L; j += kTopkThreads) raw[j] = src[j];
+      __syncthreads();
+    }
     for (int j = tid; j < L; j += kTopkThreads) {
-      const int lo = max(0, j - half), hi = min(L - 1, j + half);
-      float m = raw[lo];
-      for (int t = lo + 1; t <= hi; ++t) m = fmaxf(m, raw[t]);
-      keys[j] = order_key(m);
+      float val;
+      if (pool_w == 1) {
+        val = src[j];
+      } else {
+        const int lo = max(0, j - half), hi = min(L - 1, j + half);
+        val = raw[lo];
+        for (int t = lo + 1; t <= hi; ++t) val = fmaxf(val, raw[t]);
+      }
+      if (head_sum) {
+        const float before = hh == h_first ? 0.0f : accum[j];   // the sum starts from +0
+        accum[j] = before + val;
+      } else {
+        keys[j] = order_key(val);
+      }
     }
   }
+  if (head_sum)
+    for (int j = tid; j < L; j += kTopkThreads) keys[j] = order_key(accum[j]);
   __syncthreads();
 
   // radix select, most significant byte first: the kk-th largest among keys matching `prefix`
@@ -238,16 +267,18 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   uint32_t before = incl - packed;
   for (int w = 0; w < wave; ++w) before += wave_tot[w];
   uint32_t gt_before = before & 0xffffu, eq_before = before >> 16;
-  int32_t* __restrict__ out = idx_out + int64_t(h) * total_k + o0;
   for (int j = j0; j < j1; ++j) {
     const uint32_t key = keys[j];
+    int slot = -1;
     if (key > thr) {
-      out[gt_before + min(eq_before, need_eq)] = j;
+      slot = int(gt_before + min(eq_before, need_eq));
       ++gt_before;
     } else if (key == thr) {
-      if (eq_before < need_eq) out[gt_before + eq_before] = j;
+      if (eq_before < need_eq) slot = int(gt_before + eq_before);
       ++eq_before;
     }
+    if (slot >= 0)
+      for (int hh = h_first; hh < h_last; ++hh) idx_out[int64_t(hh) * total_k + o0 + slot] = j;
   }
 }
 
@@ -285,7 +316,8 @@ static hipError_t launch_score(const Shape& s, const void* k, const float* qsum,
 
 hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,
                          const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t max_k,
-                         int32_t pool_w, int32_t* idx_out, void* ws, hipStream_t st) {
+                         int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out, void* ws,
+                         hipStream_t st) {
   (void)max_k;
   const SelectPlan p = plan_select(s);
   float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_scores);
@@ -314,8 +346,8 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
                             hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
     if (e != hipSuccess) return e;
   }
-  topk_kernel<<<dim3(s.hq, s.batch), kTopkThreads, lds, st>>>(scores, cu_kv, cu_k, s.total_kv, total_k, pool_w,
-                                                             lpad, idx_out);
+  topk_kernel<<<dim3(head_sum ? 1 : s.hq, s.batch), kTopkThreads, lds, st>>>(
+      scores, cu_kv, cu_k, s.total_kv, total_k, pool_w, lpad, forced_tail, head_sum, s.hq, idx_out);
   return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ DLLM_F32, DLLM_BF16 = 0, 1
 DLLM_SEQ_SPARSE, DLLM_SEQ_DENSE = 0, 1
 
 EXPORTS = [
-    "dllm_hcsa_select_workspace", "dllm_hcsa_select",
+    "dllm_hcsa_select_workspace", "dllm_hcsa_select", "dllm_hcsa_select_ex",
     "dllm_hcsa_attend_workspace", "dllm_hcsa_attend",
     "dllm_dense_refresh_attend_workspace", "dllm_dense_refresh_attend",
     "dllm_hcsa_pack",
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.dllm_hcsa_select_workspace.argtypes = [P, i32]
         L.dllm_hcsa_select.restype = ctypes.c_int
         L.dllm_hcsa_select.argtypes = [P, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.dllm_hcsa_select_ex.restype = ctypes.c_int
+        L.dllm_hcsa_select_ex.argtypes = [P, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.dllm_hcsa_attend_workspace.restype = sz
         L.dllm_hcsa_attend_workspace.argtypes = [P, i32]
         L.dllm_hcsa_attend.restype = ctypes.c_int
@@ -161,6 +163,19 @@ def dllm_hcsa_select(batch: DllmBatch, cu_k: torch.Tensor, total_k: int, max_k: 
     return idx_out
 
 
+def dllm_hcsa_select_ex(batch: DllmBatch, cu_k: torch.Tensor, total_k: int, max_k: int, idx_out: torch.Tensor,
+                        pool_w: int = 1, forced_tail: int = 0, head_sum: bool = False,
+                        workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Selection with the block's own positions always kept and / or one list shared by all heads."""
+    if workspace is None:
+        workspace = _workspace(dllm_hcsa_select_workspace(batch, max_k), idx_out.device)
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _raise(lib().dllm_hcsa_select_ex(ctypes.byref(batch), _ptr(cu_k), int(total_k), int(max_k), int(pool_w),
+                                     int(forced_tail), int(bool(head_sum)), _ptr(idx_out), _ptr(workspace), nbytes,
+                                     _stream(stream)))
+    return idx_out
+
+
 def dllm_hcsa_attend_workspace(batch: DllmBatch, max_k: int) -> int:
     return int(lib().dllm_hcsa_attend_workspace(ctypes.byref(batch), int(max_k)))
 
@@ -230,6 +245,10 @@ class DeviceWorkload:
 
     def select(self, pool_w: int = 1, workspace=None):
         return dllm_hcsa_select(self.batch, self.cu_k, self.total_k, self.max_k, self.idx, pool_w, workspace)
+
+    def select_ex(self, pool_w: int = 1, forced_tail: int = 0, head_sum: bool = False, workspace=None):
+        return dllm_hcsa_select_ex(self.batch, self.cu_k, self.total_k, self.max_k, self.idx, pool_w, forced_tail,
+                                   head_sum, workspace)
 
     def attend(self, idx=None, workspace=None):
         return dllm_hcsa_attend(self.batch, self.idx if idx is None else idx, self.cu_k, self.total_k, self.max_k,

@@ -104,6 +104,20 @@ def test_attend_scalar_checks():
     assert attend_status(b, total_k=4000, max_k=4000, ws_bytes=need - 1) == hcsa.DLLM_ERR_WORKSPACE
 
 
+def test_select_ex_option_checks():
+    b = good_batch()
+    L = hcsa.lib()
+
+    def status(forced_tail=0, head_sum=0, max_k=50):
+        return L.dllm_hcsa_select_ex(ctypes.byref(b), FAKE, 100, max_k, 1, forced_tail, head_sum, FAKE, FAKE, 1 << 40, None)
+
+    assert status(forced_tail=-1) == hcsa.DLLM_ERR_INVALID_ARG
+    assert status(forced_tail=51) == hcsa.DLLM_ERR_INVALID_ARG
+    assert "forced_tail" in hcsa.last_error()
+    assert status(head_sum=2) == hcsa.DLLM_ERR_INVALID_ARG
+    assert status(head_sum=-1) == hcsa.DLLM_ERR_INVALID_ARG
+
+
 def test_pack_argument_checks():
     b = good_batch()
     L = hcsa.lib()

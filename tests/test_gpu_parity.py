@@ -311,3 +311,46 @@ def test_pack_and_packed_attend_ragged(dtype, D, Hq, Hkv):
 
 def test_pack_and_packed_attend_config3_full():
     check_pack_and_packed_attend(synth.config(3), "c3 full size")
+
+
+# ------------------------------------------------------------------ selection variants (Eq. 4 forced block, Eq. 5 shared list)
+
+def check_select_ex(w, pool_w, forced_tail, head_sum, name):
+    say(f"select_ex {name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
+        f"maxL={int(w.kv_lens.max())} pool_w={pool_w} forced_tail={forced_tail} head_sum={head_sum}")
+    dw = hcsa.DeviceWorkload(w)
+    dw.idx.fill_(-7)
+    dw.select_ex(pool_w, forced_tail, head_sum)
+    torch.cuda.synchronize()
+    got = dw.idx.cpu().numpy()
+    ref = oracle.select_ex(synth.to_bits(w.q), synth.to_bits(w.k), w.cu_q, w.cu_kv, w.cu_k, pool_w, forced_tail, head_sum)
+    if not np.array_equal(got, ref):
+        bad = np.argwhere(got != ref)
+        h, t = bad[0]
+        raise AssertionError(f"{len(bad)} of {ref.size} indices differ; first at head {h}, slot {t}: "
+                             f"gpu {got[h, t]} oracle {ref[h, t]}")
+    return dw, ref
+
+
+@pytest.mark.parametrize("pool_w,forced_tail,head_sum", [(1, 32, False), (3, 32, False), (1, 0, True), (3, 0, True),
+                                                         (3, 16, True)])
+@pytest.mark.parametrize("dtype,Hq,Hkv", [(torch.bfloat16, 8, 8), (torch.bfloat16, 8, 2), (torch.float32, 4, 4)])
+def test_select_ex_ragged(pool_w, forced_tail, head_sum, dtype, Hq, Hkv):
+    lens = [300, 65, 33, 1777, 129]
+    keep = [60, 65, 32, 500, 100]
+    w = custom(71, dtype, Hq, Hkv, 128, lens, [32, 5, 1, 32, 32], keep, salient=0.05)
+    check_select_ex(w, pool_w, forced_tail, head_sum, "ragged")
+
+
+def test_select_ex_config3_forced_block_then_attend():
+    """The denoising-loop shape of Eq. 4: the active block (last 32 positions) is always attended."""
+    w = synth.config(3)
+    dw, ref = check_select_ex(w, 1, 32, False, "c3 forced block")
+    for b in range(w.batch):
+        tail = ref[:, w.cu_k[b + 1] - 32:w.cu_k[b + 1]]
+        assert np.array_equal(tail, np.tile(np.arange(w.kv_lens[b] - 32, w.kv_lens[b]), (w.n_q_heads, 1)))
+    check_attend(w, ref, "c3 forced block", dw=dw)
+
+
+def test_select_ex_config3_head_summed():
+    check_select_ex(synth.config(3), 1, 0, True, "c3 shared list")
