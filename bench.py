@@ -6,8 +6,8 @@ One "step" is one pass of the whole hot path over resident synthetic inputs:
     dense Refresh      on the Refresh workload          (8 x L=2048, 32 heads x 128)
     select  + attend   on the mixed GQA burst           (24 Reuse + 8 Refresh sequences in one call)
 plus the paper's own Reuse layout on the first workload: pack the kept rows once, attend over the packed cache.
-The calls are interleaved (attend c3, select c5, pack c3, dense c4, select c3, packed attend c3, attend c5)
-so that every call starts with cold caches.  All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
+and the gather attend with one kept set shared by all heads (the head-summed selection of Eq. 5).
+Every call starts with cold caches: an untimed read-only pass over 512 MiB precedes it.  All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
 stream it is launched on; rates are algorithmic bytes (or flops) divided by the mean call duration.
 
 Prints ONE JSON line.  `value` is the Reuse sparse-attention rate in GB/s of algorithmic bytes
@@ -59,13 +59,22 @@ def parse():
 
 
 class Timed:
-    """A library call timed with an event pair on the current stream, once per step."""
+    """A library call timed with an event pair on the current stream, once per step.  Before the timed
+    region a read-only pass over a 512 MiB buffer evicts L2 and the 256 MB memory-side cache (and leaves
+    no dirty lines behind), so every call starts cold whatever ran before it."""
+
+    flush_buf = None
+    flush_out = None
 
     def __init__(self, name, fn):
         import torch
         self.name, self.fn, self.pairs, self.torch = name, fn, [], torch
+        if Timed.flush_buf is None:
+            Timed.flush_buf = torch.zeros(1 << 27, dtype=torch.int32, device="cuda:0")
+            Timed.flush_out = torch.zeros((), dtype=torch.int32, device="cuda:0")
 
     def __call__(self, record):
+        self.torch.max(Timed.flush_buf, out=Timed.flush_out)
         if not record:
             self.fn()
             return
@@ -82,20 +91,27 @@ class Timed:
 
 
 def cpu_baseline(w3, w4):
-    """The oracle as it stands, timed on this host: the full Reuse workload (selection and attention)
-    and a bounded sample of Refresh query rows."""
+    """The oracle as it stands, timed on this host: the full Reuse workload (selection and attention),
+    repeated for a steadier clock, and one whole Refresh sequence (all heads)."""
     import numpy as np
     import oracle
     from paper_2512_17077_amd import synth
     q, k, v = synth.to_bits(w3.q), synth.to_bits(w3.k), synth.to_bits(w3.v)
-    t0 = time.perf_counter()
-    idx = oracle.select(q, k, w3.cu_q, w3.cu_kv, w3.cu_k)
-    t1 = time.perf_counter()
-    oracle.attend(q, k, v, w3.cu_q, w3.cu_kv, idx, w3.cu_k, None, w3.softmax_scale)
-    t2 = time.perf_counter()
-    # Refresh sample: 8 query rows of the first sequence, all heads, against its full K/V
-    n = 8
+    reps = 10
+    t_sel = t_att = 0.0
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        idx = oracle.select(q, k, w3.cu_q, w3.cu_kv, w3.cu_k)
+        t1 = time.perf_counter()
+        oracle.attend(q, k, v, w3.cu_q, w3.cu_kv, idx, w3.cu_k, None, w3.softmax_scale)
+        t2 = time.perf_counter()
+        t_sel += t1 - t0
+        t_att += t2 - t1
+    t_sel /= reps
+    t_att /= reps
+    # Refresh sample: the first sequence, all query rows and heads, against its full K/V
     L = int(w4.kv_lens[0])
+    n = int(w4.q_lens[0])
     sub_q = synth.to_bits(w4.q[:n])
     sub_k, sub_v = synth.to_bits(w4.k[:L]), synth.to_bits(w4.v[:L])
     t3 = time.perf_counter()
@@ -104,13 +120,13 @@ def cpu_baseline(w3, w4):
     t4 = time.perf_counter()
     dense_flops = 4.0 * n * L * w4.head_dim * w4.n_q_heads
     return {
-        "value": w3.attend_sparse_bytes() / (t2 - t1) / 1e9,
+        "value": w3.attend_sparse_bytes() / t_att / 1e9,
         "unit": "GB/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": f"full Reuse workload {w3.name}: attend {t2 - t1:.2f} s, select {t1 - t0:.2f} s; "
-                  f"Refresh: {n} query rows x {w4.n_q_heads} heads of one L={L} sequence {t4 - t3:.2f} s",
-        "select_gbps": w3.select_bytes() / (t1 - t0) / 1e9,
+        "sample": f"full Reuse workload {w3.name}, mean of {reps} runs: attend {t_att:.3f} s, select {t_sel:.3f} s; "
+                  f"Refresh: one whole L={L} sequence ({n} query rows x {w4.n_q_heads} heads) {t4 - t3:.2f} s",
+        "select_gbps": w3.select_bytes() / t_sel / 1e9,
         "refresh_tflops": dense_flops / (t4 - t3) / 1e12,
     }
 
@@ -137,22 +153,25 @@ def main():
     ws5s = ws(hcsa.dllm_hcsa_select_workspace(d5.batch, d5.max_k))
     ws5a = ws(hcsa.dllm_hcsa_attend_workspace(d5.batch, d5.max_k))
 
-    # Call order inside a step: no call follows one that touched its inputs, so every call starts
-    # with cold caches (the 256 MB memory-side cache would otherwise serve, e.g., the K rows that the
-    # Reuse attend gathers right after selection streamed them).  In serving, selection runs at Refresh
-    # steps only and a Reuse attend finds other layers' data in the caches, never its own.
+    # Every call is preceded by an untimed read-only cache flush (see Timed), and the calls are
+    # interleaved across the workloads as well: in serving, selection runs at Refresh steps only and a
+    # Reuse attend finds other layers' data in the caches, never its own.
     sel3 = Timed("select_reuse", lambda: d3.select(workspace=ws3s))
     att3 = Timed("attend_reuse", lambda: d3.attend(workspace=ws3a))
     pack3 = Timed("pack_reuse", lambda: d3.pack())
     attp3 = Timed("attend_packed_reuse", lambda: d3.attend_packed(workspace=ws3a))
+    # the comparison point of Section 2.4 Eq. 5: one kept set shared by all heads of a sequence
+    idx_shared = torch.empty_like(d3.idx)
+    atts3 = Timed("attend_shared_list_reuse", lambda: d3.attend(idx_shared, workspace=ws3a))
     den4 = Timed("dense_refresh", lambda: d4.dense_refresh())
     sel5 = Timed("select_mixed", lambda: d5.select(workspace=ws5s))
     att5 = Timed("attend_mixed", lambda: d5.attend(workspace=ws5a))
     reuse, refresh, mixed = (args.only in ("all", w) for w in ("reuse", "refresh", "mixed"))
     calls = [c for c, on in ((att3, reuse), (sel5, mixed), (pack3, reuse), (den4, refresh), (sel3, reuse),
-                             (attp3, reuse), (att5, mixed)) if on]
+                             (attp3, reuse), (att5, mixed), (atts3, reuse)) if on]
     # the kept-row indices (and the packed cache) that the first attend calls read
     if reuse:
+        hcsa.dllm_hcsa_select_ex(d3.batch, d3.cu_k, d3.total_k, d3.max_k, idx_shared, head_sum=True, workspace=ws3s)
         d3.select(workspace=ws3s)
         d3.pack()
     if mixed:
@@ -235,6 +254,8 @@ def main():
         # the paper's layout (pack once at Refresh, then read the packed cache sequentially) beside the gather design
         "reuse_pack_gbps": pack_gbps,
         "reuse_attend_packed_gbps": packed_gbps,
+        # gather attend when all heads of a sequence share one kept set (head-summed selection, Eq. 5)
+        "reuse_attend_shared_list_gbps": rate_gbps(w3.attend_sparse_bytes(), "attend_shared_list_reuse"),
         "call_ms_mean_min": {k: [round(v[0], 5), round(v[1], 5)] for k, v in T.items()},
         # the kernel that dominates the step's time is the dense Refresh kernel (one launch per call)
         "roofline": roof("mfma", refresh_tflops, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "attend_dense_bf16_kernel",
