@@ -7,8 +7,10 @@ One "step" is one pass of the whole hot path over resident synthetic inputs:
     select  + attend   on the mixed GQA burst           (24 Reuse + 8 Refresh sequences in one call)
 plus the paper's own Reuse layout on the first workload: pack the kept rows once, attend over the packed cache.
 and the gather attend with one kept set shared by all heads (the head-summed selection of Eq. 5).
-Every call starts with cold caches: an untimed read-only pass over 512 MiB precedes it.  All inputs are on the GPU before the timed region.  Every library call is bracketed by events on the
-stream it is launched on; rates are algorithmic bytes (or flops) divided by the mean call duration.
+All inputs are on the GPU before the timed region.  A step's calls are timed call by call: the K launches
+of one call follow each other on the stream, each on the next of several copies of its inputs, so every
+launch reads its data from HBM and not from the 256 MB memory-side cache; event pairs on that stream
+bracket runs of a few launches.  Rates are algorithmic bytes (or flops) divided by the mean launch duration.
 
 Prints ONE JSON line.  `value` is the Reuse sparse-attention rate in GB/s of algorithmic bytes
 (the headline of the metric); the Refresh TFLOP/s and the other calls are reported beside it.
@@ -33,16 +35,16 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 # with the commands, is profiles/hbm_traffic_pmc.md.  They are properties of the workload shapes
 # above, not of the timing, so they are recorded here rather than re-measured on every run.
 TRAFFIC_BYTES = {
-    "attend_dense_bf16_kernel": 537.4e6,     # Refresh c4: 403.0 MB read + 134.4 MB written
+    "attend_dense_bf16_kernel": 537.3e6,     # Refresh c4: 403.0 MB read + 134.3 MB written
     "attend_sparse_bf16_kernel": 197.9e6,    # Reuse c3: 193.7 MB read + 4.2 MB written
-    "score_kernel": 287.5e6,                 # Reuse c3: 283.1 MB read + 4.5 MB written
+    "score_kernel": 287.6e6,                 # Reuse c3: 283.1 MB read + 4.5 MB written
 }
 
 # What plain kernels reach on this GPU (python -m paper_2512_17077_amd.ceilings; profiles/ceilings_microbench.md):
 # context for the fractions of the published peaks, never used as the roofline denominator.
-MEASURED_CEILINGS = {"hbm_stream_read_grid_stride_GBps": 5226.0, "hbm_stream_read_spans_nontemporal_GBps": 6572.0,
-                     "hbm_row_gather_GBps": 4822.0, "mfma_bf16_sustained_TFLOPs": 2012.0,
-                     "shader_clock_under_mfma_MHz": 1965.0}
+MEASURED_CEILINGS = {"hbm_stream_read_grid_stride_GBps": 5085.0, "hbm_stream_read_spans_nontemporal_GBps": 6530.0,
+                     "hbm_row_gather_GBps": 4718.0, "mfma_bf16_sustained_TFLOPs": 2002.0,
+                     "shader_clock_under_mfma_MHz": 1970.0}
 
 
 def parse():
@@ -53,41 +55,73 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device copy (reference launch for scaling rocprofv3 byte counters)")
+    ap.add_argument("--warm", action="store_true",
+                    help="afterwards time every call again on one copy without flushes (warm caches), for contrast")
+    ap.add_argument("--isolated", action="store_true",
+                    help="afterwards time every call again one launch at a time, each after a cache flush "
+                         "and on an otherwise idle GPU, for contrast")
     ap.add_argument("--only", choices=["all", "reuse", "refresh", "mixed"], default="all",
                     help="restrict the step to one workload (for profiling runs)")
     return ap.parse_args()
 
 
-class Timed:
-    """A library call timed with an event pair on the current stream, once per step.  Before the timed
-    region a read-only pass over a 512 MiB buffer evicts L2 and the 256 MB memory-side cache (and leaves
-    no dirty lines behind), so every call starts cold whatever ran before it."""
+class Train:
+    """One library call, launched back to back on rotating copies of its inputs.
+
+    Launches follow each other on the stream with no gap, so an event pair around a run of `chunk`
+    launches measures their kernels' durations (a pair around a single launch adds the few
+    microseconds the command processor takes between an event and the next dispatch).  Each copy has
+    its own tensors, and a call returns to a copy only after the other copies' launches have moved more
+    than the 256 MB memory-side cache holds, so every launch finds its inputs in HBM; an untimed
+    read-only pass over 512 MiB before the run evicts what earlier work left behind."""
 
     flush_buf = None
     flush_out = None
+    chunk = 5
 
-    def __init__(self, name, fn):
+    def __init__(self, name, fns):
         import torch
-        self.name, self.fn, self.pairs, self.torch = name, fn, [], torch
-        if Timed.flush_buf is None:
-            Timed.flush_buf = torch.zeros(1 << 27, dtype=torch.int32, device="cuda:0")
-            Timed.flush_out = torch.zeros((), dtype=torch.int32, device="cuda:0")
+        self.name, self.fns, self.pairs, self.torch, self.turn = name, list(fns), [], torch, 0
+        if Train.flush_buf is None:
+            Train.flush_buf = torch.zeros(1 << 27, dtype=torch.int32, device="cuda:0")
+            Train.flush_out = torch.zeros((), dtype=torch.int32, device="cuda:0")
 
-    def __call__(self, record):
-        self.torch.max(Timed.flush_buf, out=Timed.flush_out)
-        if not record:
-            self.fn()
-            return
-        a = self.torch.cuda.Event(enable_timing=True)
-        b = self.torch.cuda.Event(enable_timing=True)
-        a.record()
-        self.fn()
-        b.record()
-        self.pairs.append((a, b))
+    def launch(self):
+        self.fns[self.turn % len(self.fns)]()
+        self.turn += 1
+
+    def run(self, n, record, flush=True):
+        if flush:
+            self.torch.max(Train.flush_buf, out=Train.flush_out)
+        done = 0
+        while done < n:
+            m = min(Train.chunk, n - done)
+            if record:
+                a = self.torch.cuda.Event(enable_timing=True)
+                b = self.torch.cuda.Event(enable_timing=True)
+                a.record()
+            for _ in range(m):
+                self.launch()
+            if record:
+                b.record()
+                self.pairs.append((a, b, m))
+            done += m
+
+    def run_isolated(self, n):
+        """n launches, each after its own flush and inside its own event pair: the duration of a
+        call that starts on an idle GPU (clocks recovered, plus the event-to-dispatch latency)."""
+        for _ in range(n):
+            self.run(1, True)
 
     def ms(self):
-        t = [a.elapsed_time(b) for a, b in self.pairs]
-        return (sum(t) / len(t), min(t)) if t else (float("nan"), float("nan"))
+        """(mean per launch over all timed launches, best per-launch mean of any one event pair)"""
+        t = [(a.elapsed_time(b), m) for a, b, m in self.pairs]
+        if not t:
+            return float("nan"), float("nan")
+        return sum(x for x, _ in t) / sum(m for _, m in t), min(x / m for x, m in t)
+
+    def reset(self):
+        self.pairs = []
 
 
 def cpu_baseline(w3, w4):
@@ -144,38 +178,49 @@ def main():
     torch.cuda.set_device(0)
 
     w3, w4, w5 = synth.config(3), synth.config(4), synth.config(5)
-    d3, d4, d5 = (hcsa.DeviceWorkload(w, "cuda:0") for w in (w3, w4, w5))
+    reuse, refresh, mixed = (args.only in ("all", w) for w in ("reuse", "refresh", "mixed"))
+    # Copies per workload: a launch must not find what the launch before last left in the 256 MB
+    # memory-side cache.  A Reuse attend touches about 200 MB of its copy, a Reuse select about 290 MB:
+    # three copies; the Refresh and mixed calls move more than 500 MB each: two copies.
+    d3 = [hcsa.DeviceWorkload(w3, "cuda:0") for _ in range(3 if reuse else 0)]
+    d4 = [hcsa.DeviceWorkload(w4, "cuda:0") for _ in range(2 if refresh else 0)]
+    d5 = [hcsa.DeviceWorkload(w5, "cuda:0") for _ in range(2 if mixed else 0)]
 
     def ws(nbytes):
         return torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
-    ws3s = ws(hcsa.dllm_hcsa_select_workspace(d3.batch, d3.max_k))
-    ws3a = ws(hcsa.dllm_hcsa_attend_workspace(d3.batch, d3.max_k))
-    ws5s = ws(hcsa.dllm_hcsa_select_workspace(d5.batch, d5.max_k))
-    ws5a = ws(hcsa.dllm_hcsa_attend_workspace(d5.batch, d5.max_k))
 
-    # Every call is preceded by an untimed read-only cache flush (see Timed), and the calls are
-    # interleaved across the workloads as well: in serving, selection runs at Refresh steps only and a
-    # Reuse attend finds other layers' data in the caches, never its own.
-    sel3 = Timed("select_reuse", lambda: d3.select(workspace=ws3s))
-    att3 = Timed("attend_reuse", lambda: d3.attend(workspace=ws3a))
-    pack3 = Timed("pack_reuse", lambda: d3.pack())
-    attp3 = Timed("attend_packed_reuse", lambda: d3.attend_packed(workspace=ws3a))
-    # the comparison point of Section 2.4 Eq. 5: one kept set shared by all heads of a sequence
-    idx_shared = torch.empty_like(d3.idx)
-    atts3 = Timed("attend_shared_list_reuse", lambda: d3.attend(idx_shared, workspace=ws3a))
-    den4 = Timed("dense_refresh", lambda: d4.dense_refresh())
-    sel5 = Timed("select_mixed", lambda: d5.select(workspace=ws5s))
-    att5 = Timed("attend_mixed", lambda: d5.attend(workspace=ws5a))
-    reuse, refresh, mixed = (args.only in ("all", w) for w in ("reuse", "refresh", "mixed"))
-    calls = [c for c, on in ((att3, reuse), (sel5, mixed), (pack3, reuse), (den4, refresh), (sel3, reuse),
-                             (attp3, reuse), (att5, mixed), (atts3, reuse)) if on]
-    # the kept-row indices (and the packed cache) that the first attend calls read
+    calls = {}
     if reuse:
-        hcsa.dllm_hcsa_select_ex(d3.batch, d3.cu_k, d3.total_k, d3.max_k, idx_shared, head_sum=True, workspace=ws3s)
-        d3.select(workspace=ws3s)
-        d3.pack()
+        ws3s = ws(hcsa.dllm_hcsa_select_workspace(d3[0].batch, d3[0].max_k))
+        ws3a = ws(hcsa.dllm_hcsa_attend_workspace(d3[0].batch, d3[0].max_k))
+        # the kept-row indices, the packed cache and the shared (head-summed, Section 2.4 Eq. 5) lists of every copy
+        shared = []
+        for d in d3:
+            sh = torch.empty_like(d.idx)
+            hcsa.dllm_hcsa_select_ex(d.batch, d.cu_k, d.total_k, d.max_k, sh, head_sum=True, workspace=ws3s)
+            shared.append(sh)
+            d.select(workspace=ws3s)
+            d.pack()
+        calls["attend_reuse"] = Train("attend_reuse", [lambda d=d: d.attend(workspace=ws3a) for d in d3])
+        calls["select_reuse"] = Train("select_reuse", [lambda d=d: d.select(workspace=ws3s) for d in d3])
+        calls["pack_reuse"] = Train("pack_reuse", [lambda d=d: d.pack() for d in d3])
+        calls["attend_packed_reuse"] = Train("attend_packed_reuse",
+                                             [lambda d=d: d.attend_packed(workspace=ws3a) for d in d3])
+        calls["attend_shared_list_reuse"] = Train("attend_shared_list_reuse",
+                                                  [lambda d=d, sh=sh: d.attend(sh, workspace=ws3a)
+                                                   for d, sh in zip(d3, shared)])
+    if refresh:
+        calls["dense_refresh"] = Train("dense_refresh", [lambda d=d: d.dense_refresh() for d in d4])
     if mixed:
-        d5.select(workspace=ws5s)
+        ws5s = ws(hcsa.dllm_hcsa_select_workspace(d5[0].batch, d5[0].max_k))
+        ws5a = ws(hcsa.dllm_hcsa_attend_workspace(d5[0].batch, d5[0].max_k))
+        for d in d5:
+            d.select(workspace=ws5s)
+        calls["select_mixed"] = Train("select_mixed", [lambda d=d: d.select(workspace=ws5s) for d in d5])
+        calls["attend_mixed"] = Train("attend_mixed", [lambda d=d: d.attend(workspace=ws5a) for d in d5])
+    order = [calls[n] for n in ("select_reuse", "attend_reuse", "pack_reuse", "attend_packed_reuse",
+                                "attend_shared_list_reuse", "dense_refresh", "select_mixed", "attend_mixed")
+             if n in calls]
     torch.cuda.synchronize()
 
     if args.copy_probe:
@@ -186,18 +231,39 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        for c in calls:
-            c(False)
+    # K steps = K launches of every call; the launches of one call run as a train (see Train)
+    for c in order:
+        c.run(args.warmup, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        for c in calls:
-            c(True)
+    for c in order:
+        c.run(args.steps, True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    T = {c.name: c.ms() for c in calls}
+    T = {c.name: c.ms() for c in order}
+
+    isolated = None
+    if args.isolated:
+        for c in order:
+            c.reset()
+        for _ in range(args.steps):
+            for c in order:
+                c.run_isolated(1)
+        torch.cuda.synchronize()
+        isolated = {c.name: [round(x, 5) for x in c.ms()] for c in order}
+
+    warm = None
+    if args.warm:
+        # for contrast: the same calls with every launch on ONE copy and no flush, so that whatever
+        # fits stays in the memory-side cache between launches
+        for c in order:
+            c.reset()
+            c.fns = c.fns[:1]
+            c.run(args.warmup, False, flush=False)
+            c.run(args.steps, True, flush=False)
+        torch.cuda.synchronize()
+        warm = {c.name: [round(x, 5) for x in c.ms()] for c in order}
 
     def rate_gbps(nbytes, name):
         return nbytes / (T[name][0] * 1e-3) / 1e9 if name in T else None
@@ -235,10 +301,13 @@ def main():
         "config": {
             "workload": "c3_batched_reuse (value: Reuse attend) + c4_refresh_dense (Refresh TFLOP/s) + "
                         "c5_mixed_burst_gqa (one-call mixed dispatch)",
-            "step": [c.name for c in calls],
+            "step": [c.name for c in order],
+            "protocol": f"per call: {args.steps} launches back to back on rotating input copies, "
+                        f"one event pair per {Train.chunk} launches, cold memory-side cache",
             "reuse": {"batch": w3.batch, "heads": w3.n_q_heads, "head_dim": w3.head_dim, "block": 32,
                       "sum_kv": w3.total_kv, "sum_keep": w3.total_k,
-                      "attend_bytes": w3.attend_sparse_bytes(), "select_bytes": w3.select_bytes()},
+                      "attend_bytes": w3.attend_sparse_bytes(), "select_bytes": w3.select_bytes(),
+                      "pack_bytes": w3.pack_bytes(), "attend_packed_bytes": w3.attend_packed_bytes()},
             "refresh": {"batch": w4.batch, "heads": w4.n_q_heads, "head_dim": w4.head_dim,
                         "L": int(w4.kv_lens[0]), "flops": w4.attend_dense_flops()},
             "mixed": {"batch": w5.batch, "q_heads": w5.n_q_heads, "kv_heads": w5.n_kv_heads,
@@ -257,6 +326,8 @@ def main():
         # gather attend when all heads of a sequence share one kept set (head-summed selection, Eq. 5)
         "reuse_attend_shared_list_gbps": rate_gbps(w3.attend_sparse_bytes(), "attend_shared_list_reuse"),
         "call_ms_mean_min": {k: [round(v[0], 5), round(v[1], 5)] for k, v in T.items()},
+        "call_ms_mean_min_warm": warm,
+        "call_ms_mean_min_isolated": isolated,
         # the kernel that dominates the step's time is the dense Refresh kernel (one launch per call)
         "roofline": roof("mfma", refresh_tflops, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "attend_dense_bf16_kernel",
                          w4.attend_dense_flops()),
