@@ -176,6 +176,31 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   float* raw = reinterpret_cast<float*>(dyn + lpad);
   float* accum = reinterpret_cast<float*>(keys);
   const int half = pool_w >> 1;
+  const bool plain = pool_w == 1 && !head_sum;
+  if (plain) {
+    // plain case: eight independent loads per thread in flight, then the keys; the histogram of the
+    // leading byte (the first radix pass) is taken on the way
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    const float* __restrict__ src = scores + int64_t(h) * total_kv + kv0;
+    for (int j0 = tid; j0 < L; j0 += 8 * kTopkThreads) {
+      float x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int j = j0 + u * kTopkThreads;
+        x[u] = src[min(j, L - 1)];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int j = j0 + u * kTopkThreads;
+        if (j < L) {
+          const uint32_t key = order_key(x[u]);
+          keys[j] = key;
+          atomicAdd(&hist[key >> 24], 1u);
+        }
+      }
+    }
+  } else
   for (int hh = h_first; hh < h_last; ++hh) {
     const float* __restrict__ src = scores + int64_t(hh) * total_kv + kv0;
     if (pool_w > 1) {
@@ -209,14 +234,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   uint32_t kk = uint32_t(kb);
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    for (int j = tid; j < L; j += kTopkThreads) {
-      const uint32_t key = keys[j];
-      const bool in = pass == 0 || (key >> (shift + 8)) == prefix;
-      if (in) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    if (pass > 0 || !plain) {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int j = tid; j < L; j += kTopkThreads) {
+        const uint32_t key = keys[j];
+        const bool in = pass == 0 || (key >> (shift + 8)) == prefix;
+        if (in) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
     }
-    __syncthreads();
     if (tid < 64) {
       uint32_t c[4], t = 0;
 #pragma unroll
@@ -248,11 +275,19 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   int C = (L + kTopkThreads - 1) / kTopkThreads;
   C |= 1;
   const int j0 = min(L, tid * C), j1 = min(L, j0 + C);
+  // which of this thread's positions hold a key above / equal to the threshold (bit j - j0), when
+  // they fit 64 bits: the emit loop then visits the kept positions only
   uint32_t gt = 0, eq = 0;
+  uint64_t gt_bits = 0, eq_bits = 0;
+  const bool masks = C <= 64;
   for (int j = j0; j < j1; ++j) {
     const uint32_t key = keys[j];
     gt += key > thr;
     eq += key == thr;
+    if (masks) {
+      gt_bits |= uint64_t(key > thr) << (j - j0);
+      eq_bits |= uint64_t(key == thr) << (j - j0);
+    }
   }
   uint32_t packed = gt | (eq << 16);   // both < 2^15
   uint32_t incl = packed;
@@ -267,18 +302,28 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   uint32_t before = incl - packed;
   for (int w = 0; w < wave; ++w) before += wave_tot[w];
   uint32_t gt_before = before & 0xffffu, eq_before = before >> 16;
-  for (int j = j0; j < j1; ++j) {
-    const uint32_t key = keys[j];
+  auto emit = [&](int j, bool above) {
     int slot = -1;
-    if (key > thr) {
+    if (above) {
       slot = int(gt_before + min(eq_before, need_eq));
       ++gt_before;
-    } else if (key == thr) {
+    } else {
       if (eq_before < need_eq) slot = int(gt_before + eq_before);
       ++eq_before;
     }
     if (slot >= 0)
       for (int hh = h_first; hh < h_last; ++hh) idx_out[int64_t(hh) * total_k + o0 + slot] = j;
+  };
+  if (masks) {
+    for (uint64_t m = gt_bits | eq_bits; m != 0; m &= m - 1) {
+      const int t = __builtin_ctzll(m);
+      emit(j0 + t, (gt_bits >> t) & 1);
+    }
+  } else {
+    for (int j = j0; j < j1; ++j) {
+      const uint32_t key = keys[j];
+      if (key >= thr) emit(j, key > thr);
+    }
   }
 }
 
