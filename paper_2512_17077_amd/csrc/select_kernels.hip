@@ -339,13 +339,13 @@ SelectPlan plan_select(const Shape& s) {
 template <int ES, int D>
 static hipError_t launch_score(const Shape& s, const void* k, const float* qsum, const int32_t* cu_kv,
                                const int32_t* cu_k, float* scores, hipStream_t st) {
-  // up to four tiles per wave, as long as about four workgroups per compute unit remain
+  // Tiles per wave, once there are about four workgroups per compute unit: two, or four when a tile is
+  // scored for four or more query heads (measured on the benchmark workloads with launches back to
+  // back: one tile costs the GQA case 20 %, two cost it 10 %, four cost the one-head case 3 %).
   const int64_t wg_tiles = int64_t(s.total_kv) * s.hkv / kScoreRowsPerBlock;
+  const int tpw_max = s.group >= 4 ? 4 : 2;
   int tpw = int(wg_tiles / 1024);
-#ifndef DLLM_SCORE_TPW_MAX
-#define DLLM_SCORE_TPW_MAX 4
-#endif
-  tpw = tpw < 1 ? 1 : (tpw > DLLM_SCORE_TPW_MAX ? DLLM_SCORE_TPW_MAX : tpw);
+  tpw = tpw < 1 ? 1 : (tpw > tpw_max ? tpw_max : tpw);
   const int rows_per_block = kScoreRowsPerBlock * tpw;
   dim3 grid(s.hkv, (s.max_kv + rows_per_block - 1) / rows_per_block, s.batch);
   dim3 block(kScoreWaves * 64);
