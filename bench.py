@@ -131,7 +131,7 @@ def cpu_baseline(w3, w4):
     import oracle
     from paper_2512_17077_amd import synth
     q, k, v = synth.to_bits(w3.q), synth.to_bits(w3.k), synth.to_bits(w3.v)
-    reps = 10
+    reps = 30
     t_sel = t_att = 0.0
     for _ in range(reps):
         t0 = time.perf_counter()
@@ -169,7 +169,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); "
-              "the path shards by sequence or by head with no exchange, see DESIGN.md", file=sys.stderr)
+              "the path shards by sequence or by KV head with no exchange between GPUs", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2512_17077_amd import hcsa, synth
