@@ -136,7 +136,10 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
 }
 
 // ------------------------------------------------------------------ top-k
-constexpr int kTopkThreads = 512;
+#ifndef DLLM_TOPK_THREADS
+#define DLLM_TOPK_THREADS 512
+#endif
+constexpr int kTopkThreads = DLLM_TOPK_THREADS;
 
 __device__ __forceinline__ uint32_t order_key(float f) {
   // monotone map fp32 -> uint32 (larger float, larger key); +0 and -0 were already merged
