@@ -354,3 +354,49 @@ def test_select_ex_config3_forced_block_then_attend():
 
 def test_select_ex_config3_head_summed():
     check_select_ex(synth.config(3), 1, 0, True, "c3 shared list")
+
+
+# ------------------------------------------------------------------ HIP graph capture
+
+def test_select_and_attend_replayed_from_a_hip_graph():
+    """A serving loop captures the launch-bound step (five launches of the layer-shaped config) once and
+    replays it.  The library allocates nothing, clears nothing with memsets and never synchronises, so a
+    captured select + attend must give, on every replay and with eager work in between, exactly what
+    the eager calls give for the inputs then in the buffers (and the oracle's indices)."""
+    w = synth.config(2)
+    dw = hcsa.DeviceWorkload(w)
+    wss = torch.empty(max(256, hcsa.dllm_hcsa_select_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
+    wsa = torch.empty(max(256, hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
+    q_a = dw.q.clone()
+    q_b = torch.flip(dw.q, dims=[-1]).contiguous()   # other queries in the same buffer
+
+    def eager(qv):
+        dw.q.copy_(qv)
+        dw.select(workspace=wss)
+        dw.attend(workspace=wsa)
+        torch.cuda.synchronize()
+        return dw.idx.clone(), dw.o.clone()
+
+    ref = {"a": eager(q_a), "b": eager(q_b)}
+    assert np.array_equal(ref["a"][0].cpu().numpy(), oracle_select(w))
+    assert not torch.equal(ref["a"][0], ref["b"][0])
+
+    say("capturing select + attend of config 2")
+    graph = torch.cuda.CUDAGraph()
+    dw.q.copy_(q_a)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        dw.select(workspace=wss)
+        dw.attend(workspace=wsa)
+    for rep, which in enumerate(["a", "b", "a", "b"]):
+        say(f"replay {rep} with queries {which}")
+        dw.q.copy_(q_a if which == "a" else q_b)
+        dw.idx.fill_(-1)
+        dw.o.fill_(float("nan"))
+        busy = (dw.k.float() * 2).sum()   # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(busy)
+        assert torch.equal(dw.idx, ref[which][0]), f"replay {rep}: indices differ from the eager call"
+        assert torch.equal(dw.o, ref[which][1]), f"replay {rep}: outputs differ from the eager call"
