@@ -123,7 +123,7 @@ AttendPlan plan_attend(const Shape& s, dllm_dtype dt, int32_t max_k) {
   p.n_chunks = 1;
   if (dt == DLLM_BF16 && max_k > 0) {
     // Two workgroups of four waves fit a compute unit (512 slots on the chip).  With at least that many
-    // (sequence, head) pairs, chunks are as long as a wave's tile list allows (768 rows: six steps);
+    // (sequence, head) pairs, chunks are as long as a wave's tile list allows (2048 rows: sixteen tiles);
     // with fewer pairs, kept lists are cut finer so the chip still fills.  Chunks are multiples of the
     // 128 rows four waves take per step.
     const int64_t units = int64_t(s.batch) * s.hq;
