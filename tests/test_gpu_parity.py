@@ -229,6 +229,28 @@ def test_mixed_batch_scaled_config5():
     check_attend(w, ref, dw=dw)
 
 
+def test_batches_of_more_than_64_sequences():
+    """Above 64 sequences the kernels read their sequence's offsets directly instead of from the
+    lane-parallel table: 80 short sequences, sparse and dense mixed, ragged lengths and keep counts."""
+    rng = np.random.default_rng(31)
+    n = 80
+    lens = rng.integers(33, 260, size=n)
+    mode = (rng.random(n) < 0.25).astype(np.uint8)
+    qlens = np.where(mode == 1, lens, 32)
+    keep = np.where(mode == 1, 0, np.maximum(1, (lens * rng.uniform(0.1, 0.9, size=n)).astype(np.int64)))
+    w = custom(31, torch.bfloat16, 4, 2, 128, lens.tolist(), qlens.tolist(), keep.tolist(), mode=mode)
+    dw, ref = check_select(w)
+    check_attend(w, ref, dw=dw)
+    # the same batch through the packed layout
+    dw.pack()
+    dw.o.fill_(float("nan"))
+    sparse_rows = np.concatenate([np.arange(w.cu_q[b], w.cu_q[b + 1]) for b in range(n) if mode[b] == 0])
+    dw.attend_packed()
+    torch.cuda.synchronize()
+    got = dw.o.float().cpu().numpy()[sparse_rows]
+    assert np.abs(got - oracle_attend(w, ref)[sparse_rows]).max() <= 2e-2
+
+
 def sample_rows(w, rows_per_seq, seed):
     """Sub-workload with a few query rows of every sequence (all heads, full K/V): the oracle can
     evaluate these one by one at full benchmark size."""
