@@ -171,6 +171,7 @@ def main():
         print(f"bench.py: this build runs on one GPU only (asked for --gpus {args.gpus}); "
               "the path shards by sequence or by KV head with no exchange between GPUs", file=sys.stderr)
         sys.exit(2)
+    import numpy as np
     import torch
     from paper_2512_17077_amd import hcsa, synth
     hcsa.lib()   # raises if the HIP library is not built: there is no fallback
@@ -218,8 +219,21 @@ def main():
             d.select(workspace=ws5s)
         calls["select_mixed"] = Train("select_mixed", [lambda d=d: d.select(workspace=ws5s) for d in d5])
         calls["attend_mixed"] = Train("attend_mixed", [lambda d=d: d.attend(workspace=ws5a) for d in d5])
+        # each part of the mixed batch as a batch of its own, against its own roofline
+        w5s = synth.subset(w5, np.flatnonzero(w5.seq_mode == 0), "c5_reuse_part")
+        w5d = synth.subset(w5, np.flatnonzero(w5.seq_mode == 1), "c5_refresh_part")
+        d5s = [hcsa.DeviceWorkload(w5s, "cuda:0") for _ in range(2)]
+        d5d = [hcsa.DeviceWorkload(w5d, "cuda:0") for _ in range(2)]
+        ws5p = ws(hcsa.dllm_hcsa_attend_workspace(d5s[0].batch, d5s[0].max_k))
+        for d in d5s:
+            d.select(workspace=ws5s)
+        calls["attend_mixed_reuse_part_alone"] = Train("attend_mixed_reuse_part_alone",
+                                                       [lambda d=d: d.attend(workspace=ws5p) for d in d5s])
+        calls["attend_mixed_refresh_part_alone"] = Train("attend_mixed_refresh_part_alone",
+                                                         [lambda d=d: d.dense_refresh() for d in d5d])
     order = [calls[n] for n in ("select_reuse", "attend_reuse", "pack_reuse", "attend_packed_reuse",
-                                "attend_shared_list_reuse", "dense_refresh", "select_mixed", "attend_mixed")
+                                "attend_shared_list_reuse", "dense_refresh", "select_mixed", "attend_mixed",
+                                "attend_mixed_reuse_part_alone", "attend_mixed_refresh_part_alone")
              if n in calls]
     torch.cuda.synchronize()
 
@@ -342,8 +356,17 @@ def main():
     if "attend_mixed" in T:
         bound_ms = max(w5.attend_dense_flops() / (MFMA_BF16_PEAK_TFLOPS * 1e12),
                        w5.attend_sparse_bytes() / (HBM_PEAK_GBPS * 1e9)) * 1e3
-        out["mixed_attend"] = {"ms": T["attend_mixed"][0], "lower_bound_ms": bound_ms,
-                               "dense_tflops_if_alone": w5.attend_dense_flops() / (T["attend_mixed"][0] * 1e-3) / 1e12}
+        sparse_ms, dense_ms = T["attend_mixed_reuse_part_alone"][0], T["attend_mixed_refresh_part_alone"][0]
+        out["mixed_attend"] = {
+            "ms": T["attend_mixed"][0], "lower_bound_ms": bound_ms,
+            # the two parts as batches of their own, each against its own roofline
+            "reuse_part_alone_ms": sparse_ms,
+            "reuse_part_alone_gbps": w5.attend_sparse_bytes() / (sparse_ms * 1e-3) / 1e9,
+            "refresh_part_alone_ms": dense_ms,
+            "refresh_part_alone_tflops": w5.attend_dense_flops() / (dense_ms * 1e-3) / 1e12,
+            # the one call launches the dense part, then the sparse part, on the same stream
+            "sparse_part_hidden_under_dense_part": bool(T["attend_mixed"][0] < dense_ms + 0.5 * sparse_ms),
+            "one_call_over_sum_of_parts": T["attend_mixed"][0] / (dense_ms + sparse_ms)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w3, w4)
     print(json.dumps(out))

@@ -192,6 +192,19 @@ def make_workload(
                     cu_q, cu_kv, cu_k, seq_mode, float(softmax_scale))
 
 
+def subset(w: Workload, seqs, name: Optional[str] = None) -> Workload:
+    """The sequences `seqs` (batch positions, in the given order) of a workload as a batch of their own."""
+    seqs = [int(b) for b in seqs]
+    qrows = [torch.arange(int(w.cu_q[b]), int(w.cu_q[b + 1])) for b in seqs]
+    kvrows = [torch.arange(int(w.cu_kv[b]), int(w.cu_kv[b + 1])) for b in seqs]
+    qsel = torch.cat(qrows) if qrows else torch.zeros(0, dtype=torch.long)
+    kvsel = torch.cat(kvrows) if kvrows else torch.zeros(0, dtype=torch.long)
+    return Workload(name or w.name + "_subset", w.dtype, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                    w.q[qsel].contiguous(), w.k[kvsel].contiguous(), w.v[kvsel].contiguous(),
+                    _prefix(w.q_lens[seqs]), _prefix(w.kv_lens[seqs]), _prefix(w.keep[seqs]),
+                    w.seq_mode[seqs].copy(), w.softmax_scale)
+
+
 def config(c: int, scale_down: int = 1) -> Workload:
     """The five benchmark workloads.  `scale_down` > 1 divides sequence lengths
     (configs 3-5) to get a same-structure case the CPU oracle finishes quickly."""
