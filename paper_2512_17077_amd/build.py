@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libdllm_hcsa.so")
 SOURCES = ["api.hip", "select_kernels.hip", "pack_kernels.hip", "attend_f32.hip", "attend_sparse_bf16.hip",
            "attend_dense_bf16.hip"]
 
-# packed-fp32 VALU forms are switched off for all device code ("build flags")
+# packed-fp32 VALU forms are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-I", INCLUDE, "-I", CSRC]
