@@ -13,9 +13,11 @@
 //     tiles are XOR-swizzled by row; since the LDS side of such a load is lane-contiguous, the swizzle
 //     is applied to the global chunk each lane fetches (a permutation inside one 2*D-byte row);
 //   - K lives in a ring of three tiles (its scores are computed one step ahead), V in a ring of two;
-//   - Q is scaled by softmax_scale * log2(e) once, when it is loaded (rounded to bf16 again), and the
-//     score MFMA chain starts from the accumulator value -m (the running maximum) instead of 0, so
-//     the scores leave the matrix core ready for exp2;
+//   - the score MFMA chain starts from the accumulator value -m (the running maximum of the raw
+//     scores) instead of 0, so the scores leave the matrix core with the maximum subtracted; one
+//     multiply by softmax_scale * log2(e) per score, done in the stage that has vector slots to
+//     spare, makes them base-2 logits (Q is NOT pre-scaled: rounding the scaled queries to bf16
+//     again costs 2e-2 of output accuracy at logits around 20);
 //   - the running maximum is raised lazily (only when a score exceeds it by more than 2^8, so
 //     probabilities may exceed 1 until then) behind a uniform branch;
 //   - the key loop is unrolled over one common turn of both rings (twelve 32-key steps), so every LDS
@@ -25,7 +27,7 @@
 // in steps of 32 with a software pipeline:
 //   stage 1   S^T(i+1) = K * Q^T - m      (MFMA, A by ds_read_b128)  ||  exp2 of step i, keys 0..15
 //   stage 2   O^T += V^T P^T, keys 0..15  (MFMA, A by ds_read_b64_tr) ||  exp2 of step i, keys 16..31
-//   stage 3   O^T += V^T P^T, keys 16..31 (MFMA)                      ||  row maxima of step i+1
+//   stage 3   O^T += V^T P^T, keys 16..31 (MFMA)                      ||  scale, row maxima of step i+1
 #include <type_traits>
 
 #include "attn_tile.h"
@@ -33,6 +35,9 @@
 
 namespace dllm {
 
+#ifndef DLLM_S3V
+#define DLLM_S3V 7
+#endif
 constexpr int kDenseK = 64;          // keys per LDS tile
 constexpr int kDenseRingK = 3;       // K tiles resident in LDS
 constexpr int kDenseRingV = 2;       // V tiles resident in LDS
@@ -144,8 +149,11 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   load_tile(vbase, 0, VBASE);
   if (ntiles > 1) load_tile(kbase, 1, TILEB);
 
-  // Q^T operands: lane (col = query, hf) holds zscale * Q[query][16t + 8hf .. +8) for every step t
-  const float zscale = s.scale * kLog2e;   // > 0
+  // Q^T operands: lane (col = query, hf) holds Q[query][16t + 8hf .. +8) for every step t, as given:
+  // scaling them here would round them to bf16 a second time, an error in the logit that grows with
+  // the logit (2e-2 in the output at logits around 20); the scale is applied to the fp32 scores
+  const float zscale = s.scale * kLog2e;   // > 0; scores * zscale are base-2 logits
+  const float inv_zscale = 1.0f / zscale;
   v4u qreg[NQB][NT];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
@@ -155,15 +163,12 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     for (int t = 0; t < NT; ++t) {
       v4u x = v4u{0u, 0u, 0u, 0u};
       if (qi < nq) x = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
-      qreg[qb][t] = v4u{cvt_pk_bf16(bf16_lo(x.x) * zscale, bf16_hi(x.x) * zscale),
-                        cvt_pk_bf16(bf16_lo(x.y) * zscale, bf16_hi(x.y) * zscale),
-                        cvt_pk_bf16(bf16_lo(x.z) * zscale, bf16_hi(x.z) * zscale),
-                        cvt_pk_bf16(bf16_lo(x.w) * zscale, bf16_hi(x.w) * zscale)};
+      qreg[qb][t] = x;
     }
   }
 
-  // running maximum m (base-2 logits), kept negated in all 16 registers of an accumulator so that
-  // it can seed the score MFMA chain; row sum; output accumulators
+  // running maximum m (of the raw scores q.k), kept negated in all 16 registers of an accumulator so
+  // that it can seed the score MFMA chain; row sum; output accumulators
   f32x16 negm[NQB];
   float lsum[NQB];
   f32x16 acc[NQB][NDB];
@@ -192,6 +197,13 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) st[qb] = mfma_bf16(kop[t], qreg[qb][t], st[qb]);
   };
+  // raw scores minus the running maximum -> base-2 logits
+  auto to_logits = [&](f32x16 (&st)[NQB]) {
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st[qb][i] *= zscale;
+  };
   auto mask_tail = [&](f32x16 (&st)[NQB], int nvalid) {   // keys past the end get no weight
     asm volatile("" ::: "memory");   // keep the caller's test a real (uniform) branch
 #pragma unroll
@@ -209,16 +221,17 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     for (int i = 2; i < 16; i += 2) mx = fmaxf(fmaxf(mx, st[i]), st[i + 1]);
     return mx;
   };
-  // Raise the running maxima by delta >= 0 per query and rescale what was accumulated under the old
-  // ones, including the scores `st` already computed relative to them.
+  // Raise the running maxima by delta >= 0 (in base-2 logits) per query and rescale what was
+  // accumulated under the old ones, including the logits `st` already computed relative to them.
   auto raise = [&](f32x16 (&st)[NQB], const float (&delta)[NQB]) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
       const float alpha = __builtin_amdgcn_exp2f(-delta[qb]);
+      const float delta_raw = delta[qb] * inv_zscale;
       lsum[qb] *= alpha;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        negm[qb][i] -= delta[qb];
+        negm[qb][i] -= delta_raw;
         st[qb][i] -= delta[qb];
       }
 #pragma unroll
@@ -270,12 +283,18 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   v4u kop[NT];   // K operands of the next score chain, fetched a stage ahead of their use
   k_operands(kop, 0);
   score_chain(st_a, kop);
+  to_logits(st_a);
   if (nsteps == 1 && rem) mask_tail(st_a, rem);
-  {   // the first step sets the maxima outright (they may be negative)
-    float delta[NQB];
+  // the first step sets the maxima outright (they may be negative); nothing is accumulated yet
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) delta[qb] = max_across_halves(lane_max(st_a[qb]));
-    raise(st_a, delta);
+  for (int qb = 0; qb < NQB; ++qb) {
+    const float first = max_across_halves(lane_max(st_a[qb]));
+    const float first_raw = first * inv_zscale;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      negm[qb][i] = -first_raw;
+      st_a[qb][i] -= first;
+    }
   }
   k_operands(kop, 32 * ROWB);   // step 1 (stale LDS if there is none; then unused)
 
@@ -326,6 +345,7 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     // stage 3: O^T += V^T P^T, keys 16..31 || row maxima of step i+1 || fetch K operands of step i+2
     k_operands(kop, ((RN2 / 2) % kDenseRingK) * TILEB + (RN2 % 2) * 32 * ROWB);
     accumulate(vop1, pb1);
+    to_logits(nxt);
     bool grow = false;
     float mx[NQB];
 #pragma unroll
@@ -337,7 +357,7 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     for (int db = 0; db < NDB; ++db) {
       DLLM_SGB(kMfma, NQB);
       DLLM_SGB(kDsRead, NT / NDB);
-      DLLM_SGB(kValu, 3 * NQB);
+      DLLM_SGB(kValu, DLLM_S3V * NQB);
     }
     __builtin_amdgcn_sched_barrier(0);
     ++i;

@@ -218,6 +218,17 @@ def test_dense_small_and_ragged():
         check_attend(w, np.zeros((4, 0), np.int32), name=f"dense {dtype} D={D}")
 
 
+def test_dense_large_logits():
+    """Half of the K rows scaled by 4: base-2 logits reach +-25 and a few keys carry each query.  The
+    dense kernel keeps Q as given and scales the fp32 scores (scaling Q and rounding it to bf16 again
+    puts 2e-2 of error into the output at such logits)."""
+    w = custom(14, torch.bfloat16, 8, 2, 128, [130, 64, 700], [130, 64, 700], [0, 0, 0], mode=np.ones(3, np.uint8),
+               salient=0.5)
+    err = check_attend(w, np.zeros((8, 0), np.int32), name="dense, large logits")
+    say(f"max abs error {err:.3e}")
+    assert err <= 1.2e-2   # bf16 rounding of P and of O (|O| < 4: half an ulp is 7.8e-3) and nothing else
+
+
 def test_dense_config4_scaled():
     w = synth.config(4, scale_down=8)
     check_attend(w, np.zeros((32, 0), np.int32))
@@ -225,6 +236,19 @@ def test_dense_config4_scaled():
 
 def test_mixed_batch_scaled_config5():
     w = synth.config(5, scale_down=16)
+    dw, ref = check_select(w)
+    check_attend(w, ref, dw=dw)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(6, 2, 128), (16, 2, 128), (12, 2, 64), (5, 5, 64)])
+def test_query_heads_per_kv_head_3_8_6_1(Hq, Hkv, D):
+    """Group sizes that the score kernel walks one, two or four heads at a time (with a repeat), through
+    select, sparse attend and dense attend in one mixed batch."""
+    lens = [333, 64, 1000, 130]
+    mode = np.array([0, 0, 0, 1], np.uint8)
+    qlens = [32, 9, 32, 130]
+    keep = [100, 64, 411, 0]
+    w = custom(41, torch.bfloat16, Hq, Hkv, D, lens, qlens, keep, mode=mode, salient=0.05)
     dw, ref = check_select(w)
     check_attend(w, ref, dw=dw)
 
