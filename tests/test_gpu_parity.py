@@ -229,6 +229,32 @@ def test_dense_large_logits():
     assert err <= 1.2e-2   # bf16 rounding of P and of O (|O| < 4: half an ulp is 7.8e-3) and nothing else
 
 
+@pytest.mark.parametrize("order", ["ascending", "descending", "zero_queries", "huge"])
+def test_attend_logit_orders_that_stress_the_online_softmax(order):
+    """Keys whose logits grow along the sequence make the running maximum rise at every tile (the lazy
+    rescale fires again and again); falling ones never raise it after the first tile; zero queries give
+    the plain mean of V; logits of +-150 make the softmax one-hot.  Sparse and dense sequences in one call."""
+    lens = [700, 513, 300]
+    mode = np.array([0, 1, 0], np.uint8)
+    w = custom(15, torch.bfloat16, 4, 2, 128, lens, [32, 513, 32], [333, 0, 300], mode=mode)
+    k = w.k.float()
+    for b in range(3):
+        lo, hi = int(w.cu_kv[b]), int(w.cu_kv[b + 1])
+        ramp = torch.linspace(0.0, 1.0, hi - lo)[:, None, None]
+        if order == "ascending":
+            k[lo:hi] *= 1.0 + 7.0 * ramp
+        elif order == "descending":
+            k[lo:hi] *= 8.0 - 7.0 * ramp
+        elif order == "huge":
+            k[lo:hi] *= 12.0
+    if order == "zero_queries":
+        w.q.zero_()
+    w.k.copy_(k.to(torch.bfloat16))
+    idx = oracle_select(w)
+    err = check_attend(w, idx, name=f"logit order {order}")
+    say(f"max abs error {err:.3e}")
+
+
 def test_dense_config4_scaled():
     w = synth.config(4, scale_down=8)
     check_attend(w, np.zeros((32, 0), np.int32))
