@@ -137,6 +137,37 @@ def test_select_strided_inputs():
     assert err <= 2e-2
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_dense_and_pack_on_strided_inputs(dtype):
+    """The dense entry point and the pack on views into one fused QKV activation (two ragged sequences)."""
+    Hq, Hkv, D = 8, 2, 128
+    lens = [300, 77]
+    w = custom(16, dtype, Hq, Hkv, D, lens, lens, [0, 0], mode=np.ones(2, np.uint8))
+    T = sum(lens)
+    fused = torch.zeros((T, Hq + 2 * Hkv, D), dtype=dtype, device="cuda:0")
+    fused[:, :Hq] = w.q.cuda(); fused[:, Hq:Hq + Hkv] = w.k.cuda(); fused[:, Hq + Hkv:] = w.v.cuda()
+    q, k, v = fused[:, :Hq], fused[:, Hq:Hq + Hkv], fused[:, Hq + Hkv:]
+    cu = torch.from_numpy(w.cu_q).cuda()
+    batch = hcsa.make_batch(q, k, v, cu, cu, max(lens), max(lens), w.softmax_scale)
+    o = torch.full((T, Hq, D), float("nan"), dtype=dtype, device="cuda:0")
+    hcsa.dllm_dense_refresh_attend(batch, o)
+    torch.cuda.synchronize()
+    err = np.abs(o.float().cpu().numpy() - oracle_attend(w, np.zeros((Hq, 0), np.int32))).max()
+    assert err <= TOL[dtype]
+    # pack a per-head selection of the strided K/V and compare with the oracle's pack, bit for bit
+    keep = [120, 77]
+    ws = custom(16, dtype, Hq, Hkv, D, lens, lens, keep)   # same seed: same Q, K, V
+    assert torch.equal(ws.k, w.k)
+    idx = oracle_select(ws)
+    cu_k = torch.from_numpy(ws.cu_k).cuda()
+    kp = torch.empty((Hq, sum(keep), D), dtype=dtype, device="cuda:0")
+    vp = torch.empty_like(kp)
+    hcsa.dllm_hcsa_pack(batch, torch.from_numpy(idx).cuda(), cu_k, sum(keep), max(keep), kp, vp)
+    torch.cuda.synchronize()
+    rk, rv = oracle.pack(synth.to_bits(ws.k), synth.to_bits(ws.v), ws.cu_kv, idx, ws.cu_k)
+    assert np.array_equal(synth.to_bits(kp.cpu()), rk) and np.array_equal(synth.to_bits(vp.cpu()), rv)
+
+
 # ------------------------------------------------------------------ attention over kept rows
 
 @pytest.mark.parametrize("c", [1, 2])
