@@ -13,7 +13,7 @@
 //   S^T      = K_tile (32 keys x D) * Q^T (D x 32 queries): A and B by ds_read_b128
 //   softmax  online, base 2, lazily rescaled, per query column
 //   O^T     += V_tile^T * P^T: A by ds_read_b64_tr_b16, B = the S^T accumulators in place
-// After the loop the four waves merge (m, l, O) through LDS.  A (sequence, head) whose kept rows fit
+// After the loop the four waves merge (m, l, O) through LDS (one barrier).  A (sequence, head) whose kept rows fit
 // one chunk writes O directly; otherwise chunks write fp32 partials and a small kernel merges them.
 #include "attn_tile.h"
 
@@ -101,10 +101,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
 
   // per wave: K tile then V tile; reused as fp32 merge space afterwards
   __shared__ __attribute__((aligned(16))) char lds[kWaves][2 * TILEB];
-  // the 32 queries of the current query tile (same swizzled layout as a K tile); after the loop the
-  // waves' (m, l) pairs are exchanged through it
+  // the 32 queries of the current query tile (same swizzled layout as a K tile)
   __shared__ __attribute__((aligned(16))) char qtile[TILEB];
-  __shared__ int sm_rows[kWaves][kMaxTilesPerWave * kTile];   // kept-row ids of each wave's tiles
+  // kept-row ids of each wave's tiles; after the loop each wave leaves its (m, l) pairs in its own part
+  __shared__ int sm_rows[kWaves][kMaxTilesPerWave * kTile];
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int col = lane & 31, hf = lane >> 5;
@@ -300,31 +300,37 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
       for (int j = 0; tile < ntiles; ++j, tile += kWaves) round(kra, vra, j, tile);
     }
 
-    // ---- merge the four waves' (m, l, O^T) through LDS
+    // ---- merge the four waves' (m, l, O^T) through LDS.  Every wave leaves its own running maximum,
+    // row sum and unscaled accumulators in LDS that only it has used (its kept-row ids and its tile
+    // buffers), so one barrier is enough; the wave that reduces a head_dim block applies the factors
+    // exp2(m_w - m) while it adds.
     const float l = sum_across_halves(lsum);
-    float* sm_m = reinterpret_cast<float*>(qtile);           // [wave][32]
-    float* sm_l = reinterpret_cast<float*>(qtile) + kWaves * 32;
-    __syncthreads();                       // every wave is done with its tile buffers and with Q
-    if (hf == 0) { sm_m[wave * 32 + col] = m_used; sm_l[wave * 32 + col] = l; }
-    __syncthreads();
-    float m_all = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, sm_m[w * 32 + col]);
-    float l_all = 0.0f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) l_all += sm_l[w * 32 + col] * __builtin_amdgcn_exp2f(sm_m[w * 32 + col] - m_all);
-    const float mine = __builtin_amdgcn_exp2f(m_used - m_all);   // 0 for a wave that saw no tile
+    float* sm_ml = reinterpret_cast<float*>(&sm_rows[0][0]);   // [wave][m: 32 | l: 32], row stride = a wave's id area
+    constexpr int kMlStride = kMaxTilesPerWave * kTile;
+    if (hf == 0) {
+      sm_ml[wave * kMlStride + col] = m_used;
+      sm_ml[wave * kMlStride + 32 + col] = l;
+    }
     float4* mrg = reinterpret_cast<float4*>(&lds[0][0]);         // [wave][db][quad][lane], 16 bytes per lane
 #pragma unroll
     for (int db = 0; db < NDB; ++db)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4)
         mrg[((wave * NDB + db) * 4 + i4) * 64 + lane] =
-            make_float4(acc[db][4 * i4 + 0] * mine, acc[db][4 * i4 + 1] * mine, acc[db][4 * i4 + 2] * mine,
-                        acc[db][4 * i4 + 3] * mine);
+            make_float4(acc[db][4 * i4 + 0], acc[db][4 * i4 + 1], acc[db][4 * i4 + 2], acc[db][4 * i4 + 3]);
     __syncthreads();
     if (wave < NDB) {
       const int db = wave;
+      float m_all = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, sm_ml[w * kMlStride + col]);
+      float f[kWaves];
+      float l_all = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        f[w] = __builtin_amdgcn_exp2f(sm_ml[w * kMlStride + col] - m_all);   // 0 for a wave that saw no tile
+        l_all += sm_ml[w * kMlStride + 32 + col] * f[w];
+      }
       float outv[16];
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
@@ -332,7 +338,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
           const float4 x = mrg[((w * NDB + db) * 4 + i4) * 64 + lane];
-          a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w;
+          a.x += x.x * f[w]; a.y += x.y * f[w]; a.z += x.z * f[w]; a.w += x.w * f[w];
         }
         outv[4 * i4 + 0] = a.x; outv[4 * i4 + 1] = a.y; outv[4 * i4 + 2] = a.z; outv[4 * i4 + 3] = a.w;
       }
@@ -359,7 +365,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
         }
       }
     }
-    __syncthreads();                       // merge space becomes tile space again
+    if ((qt + 1) * 32 < nq) __syncthreads();   // merge space becomes tile space again
   }
 }
 
