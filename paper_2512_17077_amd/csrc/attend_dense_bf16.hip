@@ -436,6 +436,7 @@ hipError_t launch_attend_dense_bf16(const Shape& s, const void* q, const void* k
                                     const int32_t* cu_q, const int32_t* cu_kv, const uint8_t* seq_mode, int which,
                                     void* o, hipStream_t st) {
   constexpr int rows = kDenseWaves * 32 * kDenseQB;
+  if (s.max_q == 0) return hipSuccess;   // no sequence has a query: nothing to write
   dim3 grid((s.max_q + rows - 1) / rows, s.hq, s.batch);
   const uint16_t *qh = static_cast<const uint16_t*>(q), *kh = static_cast<const uint16_t*>(k),
                  *vh = static_cast<const uint16_t*>(v);

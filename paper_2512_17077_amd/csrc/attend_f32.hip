@@ -102,6 +102,7 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(
 hipError_t launch_attend_f32(const Shape& s, const void* q, const void* k, const void* v, const int32_t* cu_q,
                              const int32_t* cu_kv, const int32_t* idx, const int32_t* cu_k, int32_t total_k,
                              const uint8_t* seq_mode, int which, void* o, hipStream_t st) {
+  if (s.max_q == 0) return hipSuccess;   // no sequence has a query: nothing to write
   dim3 grid((s.max_q + 3) / 4, s.hq, s.batch);
   const float *qf = static_cast<const float*>(q), *kf = static_cast<const float*>(k),
               *vf = static_cast<const float*>(v);

@@ -414,6 +414,7 @@ hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const 
                                      const void* v, const int32_t* cu_q, const int32_t* cu_kv, const int32_t* idx,
                                      const int32_t* cu_k, int32_t total_k, const uint8_t* seq_mode, void* o,
                                      void* ws, hipStream_t st) {
+  if (s.max_q == 0) return hipSuccess;   // no sequence has a query: nothing to write
   char* w = static_cast<char*>(ws);
   float* po = p.n_chunks > 1 ? reinterpret_cast<float*>(w + p.off_po) : nullptr;
   float* pm = p.n_chunks > 1 ? reinterpret_cast<float*>(w + p.off_pm) : nullptr;

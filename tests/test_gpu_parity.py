@@ -459,6 +459,18 @@ def test_select_ex_config3_head_summed():
     check_select_ex(synth.config(3), 1, 0, True, "c3 shared list")
 
 
+def test_sequences_without_queries():
+    """A sequence may have no query rows this step (it only holds cache): selection then ranks a zero
+    block sum (all ties, lowest positions win), attention has nothing to write for it, and its
+    neighbours in the batch are unaffected."""
+    for dtype in (torch.bfloat16, torch.float32):
+        w = custom(17, dtype, 4, 2, 128, [100, 37, 64, 200], [0, 37, 0, 32], [40, 0, 0, 77],
+                   mode=np.array([0, 1, 1, 0], np.uint8))
+        dw, ref = check_select(w)
+        assert np.array_equal(ref[:, :40], np.tile(np.arange(40), (4, 1)))
+        check_attend(w, ref, dw=dw)
+
+
 # ------------------------------------------------------------------ HIP graph capture
 
 def test_select_and_attend_replayed_from_a_hip_graph():
