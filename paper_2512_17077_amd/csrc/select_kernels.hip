@@ -11,6 +11,9 @@
 // lane owns a whole row, each wave stages 64 rows through LDS: 16-byte chunks are loaded so that a
 // row's chunks sit in neighbouring lanes, written to LDS with an XOR swizzle, and read back one row
 // per lane without bank conflicts.
+#include <type_traits>
+#include <utility>
+
 #include "common.h"
 
 namespace dllm {
@@ -57,8 +60,49 @@ __device__ __forceinline__ int swz(int row) {
 // ES: element bytes (2 = bf16, 4 = fp32); D: head_dim; GT: query heads scored per pass over the tile.
 // Each wave walks `tiles_per_wave` consecutive 64-row tiles; while it scores one tile out of LDS the
 // next tile's rows are already in flight into registers.
+// acc += q[J + e] * kv[e] for e = 0 .. N-1 in this order, one fused multiply-add each, where q[j] is
+// what lane j of this lane's row of 16 lanes holds in `vq`: v_fmac_f32 with the DPP row broadcast
+// applied to its first operand, so the block sums reach the multiplier without scalar loads (which
+// return out of order: every wait for one is a wait for all) and without an instruction of their own.
+// The leading s_nop covers the two wait states a DPP read needs after a vector write of its source,
+// should the compiler have copied `vq` just before.
+template <int J, int N>
+__device__ __forceinline__ float fma_row_bcast(float acc, float vq, const float (&kv)[N]) {
+  static_assert(N == 4 || N == 8, "one 16-byte chunk of fp32 or bf16");
+  static_assert(J % N == 0 && J + N <= 16, "the chunk lies inside one row of 16 sums");
+  if constexpr (N == 8) {
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %1, %2 row_newbcast:%10 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %3 row_newbcast:%11 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %4 row_newbcast:%12 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %5 row_newbcast:%13 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %6 row_newbcast:%14 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %7 row_newbcast:%15 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %8 row_newbcast:%16 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %9 row_newbcast:%17 row_mask:0xf bank_mask:0xf"
+        : "+v"(acc)
+        : "v"(vq), "v"(kv[0]), "v"(kv[1]), "v"(kv[2]), "v"(kv[3]), "v"(kv[4]), "v"(kv[5]), "v"(kv[6]), "v"(kv[7]),
+          "n"(J), "n"(J + 1), "n"(J + 2), "n"(J + 3), "n"(J + 4), "n"(J + 5), "n"(J + 6), "n"(J + 7));
+  } else {
+    asm("s_nop 1\n\t"
+        "v_fmac_f32_dpp %0, %1, %2 row_newbcast:%6 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %3 row_newbcast:%7 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %4 row_newbcast:%8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %1, %5 row_newbcast:%9 row_mask:0xf bank_mask:0xf"
+        : "+v"(acc)
+        : "v"(vq), "v"(kv[0]), "v"(kv[1]), "v"(kv[2]), "v"(kv[3]), "n"(J), "n"(J + 1), "n"(J + 2), "n"(J + 3));
+  }
+  return acc;
+}
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ... in order
+template <typename F, int... C>
+__device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, C...>) {
+  (f(std::integral_constant<int, C>{}), ...);
+}
+
 template <int ES, int D, int GT>
-__global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
+__global__ __launch_bounds__(kScoreWaves * 64, (ES * D <= 256 ? 2 : 1)) void score_kernel(
     const char* __restrict__ k, const float* __restrict__ qsum, const int32_t* __restrict__ cu_kv,
     const int32_t* __restrict__ cu_k, float* __restrict__ scores, int tiles_per_wave, Shape s) {
   constexpr int ROWB = D * ES;
@@ -90,6 +134,22 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
     }
   };
   fetch(first);
+
+  // Block sums of the GT query heads scored per pass, 16 per register: lane l holds sum[16 i + l % 16]
+  // in vq[t][i] (the same in all four rows of 16 lanes).  With one pass per tile (group == GT) they
+  // are fetched once, here; with several, at the start of every pass.
+  constexpr int NQ = D / 16;
+  float vq[GT][NQ];
+  auto load_sums = [&](int hh) {
+    const float* __restrict__ qs = qsum + (int64_t(b) * s.hq + g * s.group + hh) * D + (lane & 15);
+#pragma unroll
+    for (int t = 0; t < GT; ++t)
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) vq[t][i] = qs[t * D + 16 * i];
+  };
+  const bool one_pass = s.group == GT;
+  if (one_pass) load_sums(0);
+
   for (int it = 0; it < ntiles; ++it) {
     const int r0 = first + it * 64;
 #pragma unroll
@@ -104,12 +164,13 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
 
     for (int hh = 0; hh < s.group; hh += GT) {
       const int h0 = g * s.group + hh;
-      const float* __restrict__ qs = qsum + (int64_t(b) * s.hq + h0) * D;
+      if (!one_pass) load_sums(hh);
       float acc[GT];
 #pragma unroll
       for (int t = 0; t < GT; ++t) acc[t] = 0.0f;
-#pragma unroll
-      for (int c = 0; c < CH; ++c) {
+      // one key per lane: its row, 16 bytes at a time, against the sums in ascending d
+      auto chunk = [&](auto cc) {
+        constexpr int c = decltype(cc)::value;
         const v4u x = mine[lane * CH + (c ^ sw)];
         float kv[EPC];
         if constexpr (ES == 2) {
@@ -120,11 +181,9 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_kernel(
           kv[2] = __uint_as_float(x.z); kv[3] = __uint_as_float(x.w);
         }
 #pragma unroll
-        for (int e = 0; e < EPC; ++e) {
-#pragma unroll
-          for (int t = 0; t < GT; ++t) acc[t] = __builtin_fmaf(qs[t * D + c * EPC + e], kv[e], acc[t]);
-        }
-      }
+        for (int t = 0; t < GT; ++t) acc[t] = fma_row_bcast<(c * EPC) % 16, EPC>(acc[t], vq[t][(c * EPC) / 16], kv);
+      };
+      for_each_index(chunk, std::make_integer_sequence<int, CH>{});
       if (r0 + lane < L) {
 #pragma unroll
         for (int t = 0; t < GT; ++t)
