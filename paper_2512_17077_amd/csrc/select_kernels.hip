@@ -1,8 +1,8 @@
 // Selection: per-head importance scores (Section 4.5, Eq. 6) and per-head top-k.
 //
-// Three kernels on the caller's stream:
-//   block_qsum_kernel   qsum[b,h,:] = sum of the sequence's block queries (fp32, ascending rows)
-//   score_kernel        one pass over K: s[h,j] = fma chain over d of qsum[h,d] * K[j, h/G, d]
+// Two kernels on the caller's stream:
+//   score_kernel        qsum[h,:] = sum of the sequence's block queries (fp32, ascending rows), then
+//                       one pass over K: s[h,j] = fma chain over d of qsum[h,d] * K[j, h/G, d]
 //   topk_kernel         per (sequence, head): pooled keys in LDS, radix select of the k-th largest,
 //                       ordered compaction (ties to the lower position, output ascending)
 //
@@ -17,34 +17,6 @@
 #include "common.h"
 
 namespace dllm {
-
-// ------------------------------------------------------------------ block query sum
-template <typename T>
-__device__ __forceinline__ float widen(const T* p);
-template <>
-__device__ __forceinline__ float widen<float>(const float* p) { return *p; }
-template <>
-__device__ __forceinline__ float widen<uint16_t>(const uint16_t* p) { return __uint_as_float(uint32_t(*p) << 16); }
-
-template <typename T>
-__global__ void block_qsum_kernel(const T* __restrict__ q, const int32_t* __restrict__ cu_q,
-                                  const int32_t* __restrict__ cu_k, float* __restrict__ qsum, Shape s) {
-  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  if (cu_k[b + 1] == cu_k[b]) return;
-  const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
-  const T* p = q + int64_t(q0) * s.q_tok + int64_t(h) * s.q_head + d;
-  float a = 0.0f;
-  int i = 0;
-  for (; i + 16 <= nq; i += 16) {   // 16 independent loads in flight, then the adds in row order
-    float x[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) x[j] = widen<T>(p + int64_t(i + j) * s.q_tok);
-#pragma unroll
-    for (int j = 0; j < 16; ++j) a = a + x[j];
-  }
-  for (; i < nq; ++i) a = a + widen<T>(p + int64_t(i) * s.q_tok);
-  qsum[(int64_t(b) * s.hq + h) * s.d + d] = a;
-}
 
 // ------------------------------------------------------------------ score
 constexpr int kScoreWaves = 4;
@@ -103,12 +75,14 @@ __device__ __forceinline__ void for_each_index(F& f, std::integer_sequence<int, 
 
 template <int ES, int D, int GT>
 __global__ __launch_bounds__(kScoreWaves * 64, (ES * D <= 256 ? 2 : 1)) void score_kernel(
-    const char* __restrict__ k, const float* __restrict__ qsum, const int32_t* __restrict__ cu_kv,
-    const int32_t* __restrict__ cu_k, float* __restrict__ scores, int tiles_per_wave, Shape s) {
+    const char* __restrict__ k, const char* __restrict__ q, const int32_t* __restrict__ cu_q,
+    const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k, float* __restrict__ scores,
+    int tiles_per_wave, Shape s) {
   constexpr int ROWB = D * ES;
   constexpr int CH = ROWB / 16;   // 16-byte chunks per row
   constexpr int EPC = 16 / ES;    // elements per chunk
   __shared__ v4u tile[kScoreWaves][64 * CH];
+  extern __shared__ __attribute__((aligned(16))) float sums[];   // [group][D]: block sums of this KV head's query heads
 
   // KV head is the fastest grid index: workgroups launched together read neighbouring 2*D-byte
   // slices of the same token rows, which keeps the DRAM pages they open busy
@@ -116,9 +90,9 @@ __global__ __launch_bounds__(kScoreWaves * 64, (ES * D <= 256 ? 2 : 1)) void sco
   if (cu_k[b + 1] == cu_k[b]) return;
   const int kv0 = cu_kv[b], L = cu_kv[b + 1] - kv0;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (blockIdx.y * kScoreWaves * tiles_per_wave * 64 >= L) return;   // the whole workgroup lies past the end
   const int first = (blockIdx.y * kScoreWaves + wave) * tiles_per_wave * 64;
-  if (first >= L) return;
-  const int ntiles = min(tiles_per_wave, (L - first + 63) / 64);
+  const int ntiles = first < L ? min(tiles_per_wave, (L - first + 63) / 64) : 0;   // 0: only helps with the sums
   const char* base = k + (int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head) * ES + (lane % CH) * 16;
   const int64_t row_pitch = s.kv_tok * ES;
   v4u* mine = tile[wave];
@@ -133,15 +107,45 @@ __global__ __launch_bounds__(kScoreWaves * 64, (ES * D <= 256 ? 2 : 1)) void sco
       regs[i] = load_once(base + row * row_pitch);
     }
   };
-  fetch(first);
+  if (ntiles > 0) fetch(first);
 
-  // Block sums of the GT query heads scored per pass, 16 per register: lane l holds sum[16 i + l % 16]
-  // in vq[t][i] (the same in all four rows of 16 lanes).  With one pass per tile (group == GT) they
-  // are fetched once, here; with several, at the start of every pass.
+  // While the first rows are on their way: the block sums of this KV head's query heads,
+  // sum[hh][d] = sum over the block's query rows in ascending row order, fp32 (the canonical order).
+  // Every workgroup computes the few hundred sums it needs itself (the block's queries are a few KB
+  // and stay in L2), so selection needs no reduction launch of its own.
+  {
+    const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
+    const int64_t qpitch = s.q_tok * ES;
+    auto widen = [](const char* p) -> float {
+      if constexpr (ES == 2)
+        return __uint_as_float(uint32_t(*reinterpret_cast<const uint16_t*>(p)) << 16);
+      else
+        return *reinterpret_cast<const float*>(p);
+    };
+    for (int e = threadIdx.x; e < s.group * D; e += kScoreWaves * 64) {
+      const char* p = q + (int64_t(q0) * s.q_tok + int64_t(g * s.group + e / D) * s.q_head + e % D) * ES;
+      float a = 0.0f;
+      int i = 0;
+      for (; i + 16 <= nq; i += 16) {   // 16 independent loads in flight, then the adds in row order
+        float x[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) x[j] = widen(p + (i + j) * qpitch);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) a = a + x[j];
+      }
+      for (; i < nq; ++i) a = a + widen(p + i * qpitch);
+      sums[e] = a;
+    }
+    __syncthreads();
+  }
+
+  // Sums of the GT query heads scored per pass, 16 per register: lane l holds sum[16 i + l % 16] in
+  // vq[t][i] (the same in all four rows of 16 lanes).  With one pass per tile (group == GT) they are
+  // read once, here; with several, at the start of every pass.
   constexpr int NQ = D / 16;
   float vq[GT][NQ];
   auto load_sums = [&](int hh) {
-    const float* __restrict__ qs = qsum + (int64_t(b) * s.hq + g * s.group + hh) * D + (lane & 15);
+    const float* qs = sums + hh * D + (lane & 15);
 #pragma unroll
     for (int t = 0; t < GT; ++t)
 #pragma unroll
@@ -393,14 +397,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
 SelectPlan plan_select(const Shape& s) {
   SelectPlan p;
   p.off_scores = 0;
-  p.off_qsum = align256(size_t(s.hq) * size_t(s.total_kv) * sizeof(float));
-  p.bytes = p.off_qsum + align256(size_t(s.batch) * s.hq * s.d * sizeof(float));
+  p.bytes = align256(size_t(s.hq) * size_t(s.total_kv) * sizeof(float));
   return p;
 }
 
 template <int ES, int D>
-static hipError_t launch_score(const Shape& s, const void* k, const float* qsum, const int32_t* cu_kv,
-                               const int32_t* cu_k, float* scores, hipStream_t st) {
+static hipError_t launch_score(const Shape& s, const void* k, const void* q, const int32_t* cu_q,
+                               const int32_t* cu_kv, const int32_t* cu_k, float* scores, hipStream_t st) {
   // Tiles per wave, once there are about four workgroups per compute unit: two, or four when a tile is
   // scored for four or more query heads (measured on the benchmark workloads with launches back to
   // back: one tile costs the GQA case 20 %, two cost it 10 %, four cost the one-head case 3 %).
@@ -411,14 +414,18 @@ static hipError_t launch_score(const Shape& s, const void* k, const float* qsum,
   const int rows_per_block = kScoreRowsPerBlock * tpw;
   dim3 grid(s.hkv, (s.max_kv + rows_per_block - 1) / rows_per_block, s.batch);
   dim3 block(kScoreWaves * 64);
-  const char* kp = static_cast<const char*>(k);
-  if (s.group % 4 == 0)
-    score_kernel<ES, D, 4><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, tpw, s);
-  else if (s.group % 2 == 0)
-    score_kernel<ES, D, 2><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, tpw, s);
-  else
-    score_kernel<ES, D, 1><<<grid, block, 0, st>>>(kp, qsum, cu_kv, cu_k, scores, tpw, s);
-  return hipGetLastError();
+  const char *kp = static_cast<const char*>(k), *qp = static_cast<const char*>(q);
+  const size_t sums_bytes = size_t(s.group) * D * sizeof(float);   // dynamic LDS beside the 64 * 2*D-byte tiles
+  auto launch = [&](auto kernel) -> hipError_t {
+    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, int(sums_bytes));
+    if (ea != hipSuccess) return ea;
+    kernel<<<grid, block, sums_bytes, st>>>(kp, qp, cu_q, cu_kv, cu_k, scores, tpw, s);
+    return hipGetLastError();
+  };
+  if (s.group % 4 == 0) return launch(score_kernel<ES, D, 4>);
+  if (s.group % 2 == 0) return launch(score_kernel<ES, D, 2>);
+  return launch(score_kernel<ES, D, 1>);
 }
 
 hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,
@@ -428,22 +435,13 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
   (void)max_k;
   const SelectPlan p = plan_select(s);
   float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_scores);
-  float* qsum = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_qsum);
   hipError_t e;
-
-  dim3 qgrid(s.hq, s.batch);
   if (dt == DLLM_BF16)
-    block_qsum_kernel<uint16_t><<<qgrid, s.d, 0, st>>>(static_cast<const uint16_t*>(q), cu_q, cu_k, qsum, s);
+    e = s.d == 128 ? launch_score<2, 128>(s, k, q, cu_q, cu_kv, cu_k, scores, st)
+                   : launch_score<2, 64>(s, k, q, cu_q, cu_kv, cu_k, scores, st);
   else
-    block_qsum_kernel<float><<<qgrid, s.d, 0, st>>>(static_cast<const float*>(q), cu_q, cu_k, qsum, s);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-
-  if (dt == DLLM_BF16)
-    e = s.d == 128 ? launch_score<2, 128>(s, k, qsum, cu_kv, cu_k, scores, st)
-                   : launch_score<2, 64>(s, k, qsum, cu_kv, cu_k, scores, st);
-  else
-    e = s.d == 128 ? launch_score<4, 128>(s, k, qsum, cu_kv, cu_k, scores, st)
-                   : launch_score<4, 64>(s, k, qsum, cu_kv, cu_k, scores, st);
+    e = s.d == 128 ? launch_score<4, 128>(s, k, q, cu_q, cu_kv, cu_k, scores, st)
+                   : launch_score<4, 64>(s, k, q, cu_q, cu_kv, cu_k, scores, st);
   if (e != hipSuccess) return e;
 
   const int32_t lpad = (s.max_kv + 63) & ~63;
