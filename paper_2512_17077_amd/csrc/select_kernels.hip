@@ -126,7 +126,14 @@ __global__ __launch_bounds__(kScoreWaves * 64, (ES * D <= 256 ? 2 : 1)) void sco
       const char* p = q + (int64_t(q0) * s.q_tok + int64_t(g * s.group + e / D) * s.q_head + e % D) * ES;
       float a = 0.0f;
       int i = 0;
-      for (; i + 16 <= nq; i += 16) {   // 16 independent loads in flight, then the adds in row order
+      for (; i + 32 <= nq; i += 32) {   // a whole block of 32 queries: all loads in flight, then the adds in row order
+        float x[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) x[j] = widen(p + (i + j) * qpitch);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) a = a + x[j];
+      }
+      for (; i + 16 <= nq; i += 16) {
         float x[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) x[j] = widen(p + (i + j) * qpitch);
