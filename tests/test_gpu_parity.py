@@ -515,3 +515,46 @@ def test_select_and_attend_replayed_from_a_hip_graph():
         assert torch.isfinite(busy)
         assert torch.equal(dw.idx, ref[which][0]), f"replay {rep}: indices differ from the eager call"
         assert torch.equal(dw.o, ref[which][1]), f"replay {rep}: outputs differ from the eager call"
+
+
+# ------------------------------------------------------------------ random shapes
+
+@pytest.mark.parametrize("seed", list(range(32)))
+def test_random_shapes_through_every_entry_point(seed):
+    """Seeded random batches (dtype, head_dim, head grouping, ragged lengths and keep counts, a few dense
+    sequences, pooling, forced block, shared lists): selection bit-exact, then attention over the
+    selected rows, then pack + packed attention, all against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = torch.bfloat16 if rng.random() < 0.75 else torch.float32
+    D = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    Hq = Hkv * int(rng.choice([1, 2, 3, 4, 8]))
+    nseq = int(rng.integers(1, 9))
+    lens = rng.integers(1, 900, size=nseq)
+    mode = (rng.random(nseq) < 0.2).astype(np.uint8)
+    qlens = np.where(mode == 1, np.minimum(lens, 200), rng.integers(0, 40, size=nseq))
+    keep = np.where(mode == 1, 0, np.maximum(1, (lens * rng.uniform(0.05, 1.0, size=nseq)).astype(np.int64)))
+    if mode.all():
+        mode[0], keep[0], qlens[0] = 0, max(1, lens[0] // 2), 32
+    if qlens.sum() == 0:
+        qlens[0] = 7
+    w = custom(100 + seed, dtype, Hq, Hkv, D, lens.tolist(), qlens.tolist(), keep.tolist(), mode=mode,
+               salient=float(rng.choice([0.0, 0.05])))
+    pool_w = int(rng.choice([1, 1, 3, 5]))
+    head_sum = bool(rng.random() < 0.25)
+    sparse_keep = keep[mode == 0]
+    forced_tail = int(rng.integers(0, sparse_keep.min() + 1)) if rng.random() < 0.3 else 0
+    dw, ref = check_select_ex(w, pool_w, forced_tail, head_sum, f"random {seed}")
+    check_attend(w, ref, dw=dw)
+    # the packed layout of the same selection (dense sequences keep nothing and are not packed)
+    dw.pack()
+    torch.cuda.synchronize()
+    kp, vp = oracle.pack(synth.to_bits(w.k), synth.to_bits(w.v), w.cu_kv, ref, w.cu_k)
+    assert np.array_equal(synth.to_bits(dw.k_packed.cpu()), kp) and np.array_equal(synth.to_bits(dw.v_packed.cpu()), vp)
+    dw.o.fill_(float("nan"))
+    dw.attend_packed()
+    torch.cuda.synchronize()
+    rows = np.concatenate([np.arange(w.cu_q[b], w.cu_q[b + 1]) for b in range(nseq) if mode[b] == 0] + [np.zeros(0, np.int64)]).astype(np.int64)
+    if len(rows):
+        got = dw.o.float().cpu().numpy()[rows]
+        assert np.abs(got - oracle_attend(w, ref)[rows]).max() <= TOL[dtype]
