@@ -26,7 +26,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 // ---- selection (select_kernels.hip)
 struct SelectPlan {
-  size_t off_scores, bytes;
+  size_t off_scores, off_summed, bytes;
 };
 SelectPlan plan_select(const Shape& s);
 hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,

@@ -205,6 +205,33 @@ __global__ __launch_bounds__(kScoreWaves * 64, (ES * D <= 256 ? 2 : 1)) void sco
   }
 }
 
+// ------------------------------------------------------------------ head sum (Section 2.4 Eq. 5)
+// summed[kv0 + j] = sum over query heads, ascending and starting from +0, of the pooled score of
+// candidate j (the window clipped to the candidates): one thread per position, so the shared
+// selection ranks one pre-summed row per sequence instead of walking every head inside the top-k.
+__global__ __launch_bounds__(256) void head_sum_kernel(const float* __restrict__ scores,
+                                                       const int32_t* __restrict__ cu_kv,
+                                                       const int32_t* __restrict__ cu_k, int32_t total_kv,
+                                                       int32_t pool_w, int32_t forced_tail, int32_t n_heads,
+                                                       float* __restrict__ summed) {
+  const int b = blockIdx.y;
+  if (cu_k[b + 1] == cu_k[b]) return;
+  const int kv0 = cu_kv[b];
+  const int L = cu_kv[b + 1] - kv0 - forced_tail;   // candidates
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= L) return;
+  const int half = pool_w >> 1;
+  const int lo = max(0, j - half), hi = min(L - 1, j + half);
+  float acc = 0.0f;
+  for (int hh = 0; hh < n_heads; ++hh) {
+    const float* __restrict__ src = scores + int64_t(hh) * total_kv + kv0;
+    float val = src[lo];
+    for (int t = lo + 1; t <= hi; ++t) val = fmaxf(val, src[t]);
+    acc = acc + val;
+  }
+  summed[kv0 + j] = acc;
+}
+
 // ------------------------------------------------------------------ top-k
 #ifndef DLLM_TOPK_THREADS
 #define DLLM_TOPK_THREADS 512
@@ -219,8 +246,9 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 
 // forced_tail: the last forced_tail positions of the sequence are kept without being ranked (the
 // active block's own rows, Section 2.3 Eq. 4); the other kept rows are chosen among the positions
-// before them.  head_sum: one list per sequence from the scores summed over the n_heads query heads
-// (Section 2.4 Eq. 5), written to every head; the grid then has one workgroup per sequence.
+// before them.  head_sum: `scores` is the row of sums over the query heads (Section 2.4 Eq. 5,
+// head_sum_kernel; pooling already applied, so pool_w is 1), ranked once per sequence and written to
+// all n_heads heads; the grid then has one workgroup per sequence.
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k,
     int32_t total_kv, int32_t total_k, int32_t pool_w, int32_t lpad, int32_t forced_tail, int32_t head_sum,
@@ -244,18 +272,17 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     for (int hh = h_first; hh < h_last; ++hh) idx_out[int64_t(hh) * total_k + o0 + kb + t] = L + t;
   if (kb <= 0) return;
 
-  // pooled score of every candidate -> order-preserving key.  A thread owns positions tid, tid + 512, ...
-  // through all of this, so the head sum needs no exchange; only the pooling window reads neighbours.
+  // (pooled) score of every candidate -> order-preserving key.  With head_sum the scores are the
+  // pre-summed (and pre-pooled) row of the sequence, ranked like one head's plain scores.
   float* raw = reinterpret_cast<float*>(dyn + lpad);
-  float* accum = reinterpret_cast<float*>(keys);
   const int half = pool_w >> 1;
-  const bool plain = pool_w == 1 && !head_sum;
+  const bool plain = pool_w == 1;
+  const float* __restrict__ src = scores + int64_t(head_sum ? 0 : h) * total_kv + kv0;
   if (plain) {
-    // plain case: eight independent loads per thread in flight, then the keys; the histogram of the
-    // leading byte (the first radix pass) is taken on the way
+    // eight independent loads per thread in flight, then the keys; the histogram of the leading byte
+    // (the first radix pass) is taken on the way
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    const float* __restrict__ src = scores + int64_t(h) * total_kv + kv0;
     for (int j0 = tid; j0 < L; j0 += 8 * kTopkThreads) {
       float x[8];
 #pragma unroll
@@ -273,33 +300,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
         }
       }
     }
-  } else
-  for (int hh = h_first; hh < h_last; ++hh) {
-    const float* __restrict__ src = scores + int64_t(hh) * total_kv + kv0;
-    if (pool_w > 1) {
-      if (hh != h_first) __syncthreads();   // everyone is done with the previous head's raw scores
-      for (int j = tid; j < L; j += kTopkThreads) raw[j] = src[j];
-      __syncthreads();
-    }
+  } else {
+    for (int j = tid; j < L; j += kTopkThreads) raw[j] = src[j];
+    __syncthreads();
     for (int j = tid; j < L; j += kTopkThreads) {
-      float val;
-      if (pool_w == 1) {
-        val = src[j];
-      } else {
-        const int lo = max(0, j - half), hi = min(L - 1, j + half);
-        val = raw[lo];
-        for (int t = lo + 1; t <= hi; ++t) val = fmaxf(val, raw[t]);
-      }
-      if (head_sum) {
-        const float before = hh == h_first ? 0.0f : accum[j];   // the sum starts from +0
-        accum[j] = before + val;
-      } else {
-        keys[j] = order_key(val);
-      }
+      const int lo = max(0, j - half), hi = min(L - 1, j + half);
+      float val = raw[lo];
+      for (int t = lo + 1; t <= hi; ++t) val = fmaxf(val, raw[t]);
+      keys[j] = order_key(val);
     }
   }
-  if (head_sum)
-    for (int j = tid; j < L; j += kTopkThreads) keys[j] = order_key(accum[j]);
   __syncthreads();
 
   // radix select, most significant byte first: the kk-th largest among keys matching `prefix`
@@ -404,7 +414,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
 SelectPlan plan_select(const Shape& s) {
   SelectPlan p;
   p.off_scores = 0;
-  p.bytes = align256(size_t(s.hq) * size_t(s.total_kv) * sizeof(float));
+  p.off_summed = align256(size_t(s.hq) * size_t(s.total_kv) * sizeof(float));   // one row of head sums (Eq. 5)
+  p.bytes = p.off_summed + align256(size_t(s.total_kv) * sizeof(float));
   return p;
 }
 
@@ -451,6 +462,15 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
                    : launch_score<4, 64>(s, k, q, cu_q, cu_kv, cu_k, scores, st);
   if (e != hipSuccess) return e;
 
+  const float* ranked = scores;
+  if (head_sum) {   // sum (pooled) scores over the heads first; the top-k then ranks one plain row per sequence
+    float* summed = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_summed);
+    head_sum_kernel<<<dim3((s.max_kv + 255) / 256, s.batch), 256, 0, st>>>(scores, cu_kv, cu_k, s.total_kv, pool_w,
+                                                                           forced_tail, s.hq, summed);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    ranked = summed;
+    pool_w = 1;
+  }
   const int32_t lpad = (s.max_kv + 63) & ~63;
   const size_t lds = size_t(lpad) * 4 * (pool_w == 1 ? 1 : 2);
   if (lds > 64 * 1024) {   // beyond the default dynamic-LDS limit: raise it for this kernel on this device
@@ -459,7 +479,7 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
     if (e != hipSuccess) return e;
   }
   topk_kernel<<<dim3(head_sum ? 1 : s.hq, s.batch), kTopkThreads, lds, st>>>(
-      scores, cu_kv, cu_k, s.total_kv, total_k, pool_w, lpad, forced_tail, head_sum, s.hq, idx_out);
+      ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, lpad, forced_tail, head_sum, s.hq, idx_out);
   return hipGetLastError();
 }
 
