@@ -301,7 +301,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
       }
     }
   } else {
-    for (int j = tid; j < L; j += kTopkThreads) raw[j] = src[j];
+    for (int j0 = tid; j0 < L; j0 += 8 * kTopkThreads) {   // eight independent loads per thread in flight
+      float x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) x[u] = src[min(j0 + u * kTopkThreads, L - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (j0 + u * kTopkThreads < L) raw[j0 + u * kTopkThreads] = x[u];
+    }
     __syncthreads();
     for (int j = tid; j < L; j += kTopkThreads) {
       const int lo = max(0, j - half), hi = min(L - 1, j + half);
