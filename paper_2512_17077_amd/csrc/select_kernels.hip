@@ -255,6 +255,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     int32_t n_heads, int32_t* __restrict__ idx_out) {
   extern __shared__ uint32_t dyn[];
   __shared__ uint32_t hist[256];
+  // The leading byte of a score (sign and seven exponent bits) takes only a handful of values, and LDS
+  // atomics of one instruction that hit one bank are served one after the other.  The first pass
+  // therefore counts into 16 copies of the histogram, chosen by lane, that lie in 16 different banks.
+  constexpr int kCopies = 16;
+  __shared__ uint32_t hist0[256 * kCopies];
   __shared__ uint32_t wave_tot[kTopkThreads / 64];
   __shared__ uint32_t sh_prefix, sh_k;
 
@@ -281,7 +286,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   if (plain) {
     // eight independent loads per thread in flight, then the keys; the histogram of the leading byte
     // (the first radix pass) is taken on the way
-    if (tid < 256) hist[tid] = 0;
+    for (int t = tid; t < 256 * kCopies; t += kTopkThreads) hist0[t] = 0;
     __syncthreads();
     for (int j0 = tid; j0 < L; j0 += 8 * kTopkThreads) {
       float x[8];
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
         if (j < L) {
           const uint32_t key = order_key(x[u]);
           keys[j] = key;
-          atomicAdd(&hist[key >> 24], 1u);
+          atomicAdd(&hist0[(key >> 24) * kCopies + (tid & (kCopies - 1))], 1u);
         }
       }
     }
@@ -324,13 +329,27 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   uint32_t kk = uint32_t(kb);
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    if (pass > 0 || !plain) {
+    if (pass == 0) {
+      if (!plain) {   // (the plain path counted while it built the keys)
+        for (int t = tid; t < 256 * kCopies; t += kTopkThreads) hist0[t] = 0;
+        __syncthreads();
+        for (int j = tid; j < L; j += kTopkThreads)
+          atomicAdd(&hist0[(keys[j] >> 24) * kCopies + (tid & (kCopies - 1))], 1u);
+      }
+      __syncthreads();
+      if (tid < 256) {
+        uint32_t t = 0;
+#pragma unroll
+        for (int c = 0; c < kCopies; ++c) t += hist0[tid * kCopies + c];
+        hist[tid] = t;
+      }
+      __syncthreads();
+    } else {   // later digits are spread evenly: one histogram, and no folding, is cheaper
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
       for (int j = tid; j < L; j += kTopkThreads) {
         const uint32_t key = keys[j];
-        const bool in = pass == 0 || (key >> (shift + 8)) == prefix;
-        if (in) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        if ((key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
       }
       __syncthreads();
     }
