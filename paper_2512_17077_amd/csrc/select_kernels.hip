@@ -1,10 +1,13 @@
 // Selection: per-head importance scores (Section 4.5, Eq. 6) and per-head top-k.
 //
-// Two kernels on the caller's stream:
+// Kernels on the caller's stream:
 //   score_kernel        qsum[h,:] = sum of the sequence's block queries (fp32, ascending rows), then
 //                       one pass over K: s[h,j] = fma chain over d of qsum[h,d] * K[j, h/G, d]
-//   topk_kernel         per (sequence, head): pooled keys in LDS, radix select of the k-th largest,
-//                       ordered compaction (ties to the lower position, output ascending)
+//   head_sum_kernel     (head-summed selection only, Section 2.4 Eq. 5) the pooled scores summed over heads
+//   topk_reg_kernel     per (sequence, head), lists of up to 4096 candidates: pooled keys in registers,
+//                       radix select of the k-th largest, ordered compaction (ties to the lower
+//                       position, output ascending)
+//   topk_kernel         the same for longer lists, with the keys in LDS
 //
 // The score arithmetic is fixed (one fused multiply-add per d, ascending d, one lane owns one key),
 // because the kept set must be reproducible bit for bit.  To keep the HBM reads coalesced while one
@@ -244,6 +247,23 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave (all lanes active) through the data-parallel
+// primitives: shifts by 1, 2, 4, 8 within each row of 16 lanes, then the last lane of row 0 (2) is
+// added to row 1 (3), then lane 31 to rows 2 and 3.  A lane without a source adds zero.
+template <int Ctrl, int RowMask>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t x) {
+  return x + uint32_t(__builtin_amdgcn_update_dpp(0, int(x), Ctrl, RowMask, 0xf, false));
+}
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
+  x = dpp_add<0x111, 0xf>(x);   // row_shr:1
+  x = dpp_add<0x112, 0xf>(x);   // row_shr:2
+  x = dpp_add<0x114, 0xf>(x);   // row_shr:4
+  x = dpp_add<0x118, 0xf>(x);   // row_shr:8
+  x = dpp_add<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 // forced_tail: the last forced_tail positions of the sequence are kept without being ranked (the
 // active block's own rows, Section 2.3 Eq. 4); the other kept rows are chosen among the positions
 // before them.  head_sum: `scores` is the row of sums over the query heads (Section 2.4 Eq. 5,
@@ -357,13 +377,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
       uint32_t c[4], t = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) { c[i] = hist[255 - (4 * tid + i)]; t += c[i]; }
-      uint32_t incl = t;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off);
-        if (tid >= off) incl += up;
-      }
-      uint32_t run = incl - t;
+      uint32_t run = wave_inclusive_sum(t) - t;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         if (run < kk && kk <= run + c[i]) {
@@ -399,13 +413,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     }
   }
   uint32_t packed = gt | (eq << 16);   // both < 2^15
-  uint32_t incl = packed;
+  const uint32_t incl = wave_inclusive_sum(packed);
   const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t up = __shfl_up(incl, off);
-    if (lane >= off) incl += up;
-  }
   if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
   uint32_t before = incl - packed;
@@ -432,6 +441,163 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     for (int j = j0; j < j1; ++j) {
       const uint32_t key = keys[j];
       if (key >= thr) emit(j, key > thr);
+    }
+  }
+}
+
+// Lists of up to R * T candidates: the same selection by a workgroup of T threads with the keys held in
+// registers (thread t owns positions t, t + T, ...), so that no pass re-reads them from LDS.  Every wave scans
+// the histogram of a pass for itself (the chosen digit is the same in all of them), which leaves one
+// barrier per pass; the four histograms are cleared once, before the scores arrive.  The ordered
+// compaction counts kept rows per (round, wave) with ballots, and every wave takes the prefix sums of
+// those counts itself.  Positions past the end of the list hold key 0, the smallest: they are not counted
+// in the first pass, and wherever later passes count them (in digit 0) they stand below every real key
+// and, among equal keys, behind every real position, so they change neither the threshold nor the list.
+template <int R, int T>
+__global__ __launch_bounds__(T) void topk_reg_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k,
+    int32_t total_kv, int32_t total_k, int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t n_heads,
+    int32_t* __restrict__ idx_out) {
+  constexpr int kCopies = 16, kWaves = T / 64;
+  constexpr int E = R * kWaves / 64;   // (round, wave) counts per lane in the final scan
+  static_assert(T >= 256 && R * kWaves % 64 == 0 && (E == 1 || E == 2), "one or two counts per lane");
+  extern __shared__ uint32_t dyn[];   // pooled selection only: the raw scores of the list
+  __shared__ __align__(16) uint32_t hist0[256 * kCopies];   // first pass, bank-separated copies (see topk_kernel)
+  __shared__ __align__(16) uint32_t hist[4][256];           // [0]: the folded first pass
+  __shared__ uint32_t counts[R * kWaves];
+
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int o0 = cu_k[b], kb_all = cu_k[b + 1] - o0;
+  if (kb_all == 0) return;
+  const int kv0 = cu_kv[b];
+  const int L = cu_kv[b + 1] - kv0 - forced_tail;
+  const int kb = kb_all - forced_tail;
+  const int h_first = head_sum ? 0 : h, h_last = head_sum ? n_heads : h + 1;
+  for (int t = tid; t < forced_tail; t += T)
+    for (int hh = h_first; hh < h_last; ++hh) idx_out[int64_t(hh) * total_k + o0 + kb + t] = L + t;
+  if (kb <= 0) return;
+
+  const float* __restrict__ src = scores + int64_t(head_sum ? 0 : h) * total_kv + kv0;
+  for (int t = tid; t < 256 * kCopies; t += T) hist0[t] = 0;
+  for (int t = tid; t < 3 * 256; t += T) (&hist[1][0])[t] = 0;
+
+  uint32_t key[R];
+  float x[R];
+#pragma unroll
+  for (int u = 0; u < R; ++u)
+    if (u * T < L) x[u] = src[min(tid + u * T, L - 1)];
+  if (pool_w != 1) {
+    float* raw = reinterpret_cast<float*>(dyn);
+    const int half = pool_w >> 1;
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      if (tid + u * T < L) raw[tid + u * T] = x[u];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      const int j = tid + u * T;
+      if (j < L) {
+        const int lo = max(0, j - half), hi = min(L - 1, j + half);
+        float val = raw[lo];
+        for (int t = lo + 1; t <= hi; ++t) val = fmaxf(val, raw[t]);
+        x[u] = val;
+      }
+    }
+  } else {
+    __syncthreads();   // histograms cleared
+  }
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    key[u] = 0;
+    if (tid + u * T < L) {
+      key[u] = order_key(x[u]);
+      atomicAdd(&hist0[(key[u] >> 24) * kCopies + (tid & (kCopies - 1))], 1u);
+    }
+  }
+  __syncthreads();
+  if (tid < 256) {
+    const uint4* c4 = reinterpret_cast<const uint4*>(hist0 + tid * kCopies);
+    uint32_t t = 0;
+#pragma unroll
+    for (int c = 0; c < kCopies / 4; ++c) {
+      const uint4 v = c4[c];
+      t += v.x + v.y + v.z + v.w;
+    }
+    hist[0][tid] = t;
+  }
+  __syncthreads();
+
+  // the digit (bin) that holds the kk-th largest of the keys counted in hrow, found by every wave
+  uint32_t prefix = 0, kk = uint32_t(kb);
+  auto pick = [&](const uint32_t* hrow) {
+    const uint4 v = *reinterpret_cast<const uint4*>(hrow + 252 - 4 * lane);
+    const uint32_t c[4] = {v.w, v.z, v.y, v.x};   // bins 255 - 4 lane - i, descending
+    const uint32_t t = c[0] + c[1] + c[2] + c[3];
+    uint32_t run = wave_inclusive_sum(t) - t;
+    uint32_t bin = 0, knew = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (run < kk && kk <= run + c[i]) {
+        found = true;
+        bin = uint32_t(255 - (4 * lane + i));
+        knew = kk - run;
+      }
+      run += c[i];
+    }
+    const uint64_t m = __ballot(found);   // one lane, since 1 <= kk <= number of keys counted
+    const int owner = m ? __builtin_ctzll(m) : 0;
+    prefix = (prefix << 8) | uint32_t(__builtin_amdgcn_readlane(int(bin), owner));
+    kk = uint32_t(__builtin_amdgcn_readlane(int(knew), owner));
+  };
+  pick(hist[0]);
+#pragma unroll
+  for (int pass = 1; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+      if ((key[u] >> (shift + 8)) == prefix)
+        atomicAdd(&hist[pass][(key[u] >> shift) & 255u], 1u);
+    __syncthreads();
+    pick(hist[pass]);
+  }
+  const uint32_t thr = prefix, need_eq = kk;
+
+  // ordered compaction: kept rows before round u of this wave, as (above | equal << 16)
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    const uint64_t bg = __ballot(key[u] > thr), be = __ballot(key[u] == thr);
+    const uint32_t c = uint32_t(__builtin_popcountll(bg)) | (uint32_t(__builtin_popcountll(be)) << 16);
+    if (lane == 0) counts[u * kWaves + wave] = c;
+  }
+  __syncthreads();
+  uint32_t c0 = counts[lane * E], c1 = E == 2 ? counts[lane * E + 1] : 0u;
+  const uint32_t excl = wave_inclusive_sum(c0 + c1) - (c0 + c1);
+  int32_t* __restrict__ out = idx_out + int64_t(h_first) * total_k + o0;
+#pragma unroll
+  for (int u = 0; u < R; ++u) {
+    if (u * T >= L) break;
+    const int e = u * kWaves + wave;
+    uint32_t base = uint32_t(__builtin_amdgcn_readlane(int(excl), e / E));
+    if (E == 2 && (e & 1)) base += uint32_t(__builtin_amdgcn_readlane(int(c0), e / E));
+    const bool gt = key[u] > thr, eq = key[u] == thr;
+    const uint64_t bg = __ballot(gt), be = __ballot(eq);
+    const uint32_t gt_before =
+        (base & 0xffffu) + __builtin_amdgcn_mbcnt_hi(uint32_t(bg >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(bg), 0u));
+    // a key above the threshold goes behind the kept rows before it; without a key equal to the
+    // threshold in this wave's round (the usual case) that is all there is to do
+    uint32_t slot = gt_before + min(base >> 16, need_eq);
+    bool keep = gt;
+    if (be != 0) {
+      const uint32_t eq_before =
+          (base >> 16) + __builtin_amdgcn_mbcnt_hi(uint32_t(be >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(be), 0u));
+      slot = gt_before + (gt ? min(eq_before, need_eq) : eq_before);
+      keep = gt || (eq && eq_before < need_eq);
+    }
+    if (keep) {
+      out[slot] = tid + u * T;
+      for (int hh = h_first + 1; hh < h_last; ++hh) out[int64_t(hh - h_first) * total_k + slot] = tid + u * T;
     }
   }
 }
@@ -497,14 +663,23 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
     ranked = summed;
     pool_w = 1;
   }
+  const dim3 grid(head_sum ? 1 : s.hq, s.batch);
   const int32_t lpad = (s.max_kv + 63) & ~63;
+  if (s.max_kv <= 8 * kTopkThreads) {
+    // Keys in registers.  (Sixteen keys per thread for lists of up to 8192 measured slower than the
+    // kernel below on the mixed workload, 20.5 against 18.1 us, although each workgroup took less time:
+    // a compute unit held fewer of them at once.  Thirty-two per thread in four waves took 25 us.)
+    topk_reg_kernel<8, kTopkThreads><<<grid, kTopkThreads, pool_w == 1 ? 0 : size_t(lpad) * 4, st>>>(
+        ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, forced_tail, head_sum, s.hq, idx_out);
+    return hipGetLastError();
+  }
   const size_t lds = size_t(lpad) * 4 * (pool_w == 1 ? 1 : 2);
   if (lds > 64 * 1024) {   // beyond the default dynamic-LDS limit: raise it for this kernel on this device
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
     if (e != hipSuccess) return e;
   }
-  topk_kernel<<<dim3(head_sum ? 1 : s.hq, s.batch), kTopkThreads, lds, st>>>(
+  topk_kernel<<<grid, kTopkThreads, lds, st>>>(
       ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, lpad, forced_tail, head_sum, s.hq, idx_out);
   return hipGetLastError();
 }

@@ -114,6 +114,16 @@ def test_select_maximum_lengths():
     check_select(w2, pool_w=3)
 
 
+@pytest.mark.parametrize("pool_w", [1, 3])
+def test_select_list_lengths_around_4096(pool_w):
+    # lists of up to 4096 positions and longer ones are ranked by different kernels
+    w = custom(6, torch.bfloat16, 4, 2, 64, [4096, 4095, 3585, 7], [32, 32, 32, 32], [4096, 1, 2000, 7])
+    w.k[4096 + 100:4096 + 164] = w.k[4096:4096 + 64].clone()      # ties
+    check_select(w, pool_w=pool_w)
+    w2 = custom(7, torch.bfloat16, 4, 2, 64, [4097, 4096, 8192], [32, 32, 32], [4097, 1000, 4000])
+    check_select(w2, pool_w=pool_w)
+
+
 def test_select_strided_inputs():
     """q/k/v as views into one fused QKV activation, the layout a model layer would hand over."""
     Hq, Hkv, D, L = 8, 2, 128, 777
