@@ -121,6 +121,7 @@ AttendPlan plan_attend(const Shape& s, dllm_dtype dt, int32_t max_k) {
   AttendPlan p{};
   p.chunk_rows = max_k > 0 ? max_k : 1;
   p.n_chunks = 1;
+  p.max_k = max_k;
   if (dt == DLLM_BF16 && max_k > 0) {
     // Two workgroups of four waves fit a compute unit (512 slots on the chip).  With at least that many
     // (sequence, head) pairs, chunks are as long as a wave's tile list allows (2048 rows: sixteen tiles);

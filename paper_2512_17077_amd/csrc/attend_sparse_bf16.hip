@@ -4,23 +4,30 @@
 // The step is bound by HBM: every kept (head, row) pair costs one 2*D-byte K row and one V row and
 // only 4*Bq*D flop.  What decides its speed is how many gathered rows are in flight, so the registers
 // go to the gathers: a workgroup of four waves walks one chunk of one (sequence, head)'s kept rows,
-// each wave owns its own 32-row tiles (no workgroup barrier in the loop) and keeps TWO tiles of K and
-// V rows in flight in registers; the queries, which every step needs again, live in LDS instead.
+// each wave owns its own 32-row tiles (no workgroup barrier in the loop) and keeps its next tile of K
+// and V rows in flight in registers; the queries, which every step needs again, live in LDS instead.
 //   gather   idx -> row offsets (32-bit, from a uniform base); 16-byte non-temporal loads with a row's
 //            chunks in neighbouring lanes (whole 256-byte rows per 16 lanes)
 //   stage    registers -> the wave's private LDS tile, XOR-swizzled by row; the freed registers are
-//            refilled with the tile after next at once
+//            refilled with the next tile at once
 //   S^T      = K_tile (32 keys x D) * Q^T (D x 32 queries): A and B by ds_read_b128
 //   softmax  online, base 2, lazily rescaled, per query column
 //   O^T     += V_tile^T * P^T: A by ds_read_b64_tr_b16, B = the S^T accumulators in place
 // After the loop the four waves merge (m, l, O) through LDS (one barrier).  A (sequence, head) whose kept rows fit
 // one chunk writes O directly; otherwise chunks write fp32 partials and a small kernel merges them.
+//
+// Two kernels share that tile arithmetic: attend_sparse_bf16_kernel gives every (sequence, head, chunk)
+// a workgroup of its own; attend_sparse_multi_bf16_kernel, for batches with more lists than compute
+// units and lists of unequal length, runs one eight-wave workgroup per compute unit that walks a
+// length-balanced share of the lists back to back.
 #include "attn_tile.h"
 
 namespace dllm {
 
 constexpr int kTile = 32;        // kept rows per wave tile
 constexpr int kWaves = 4;
+constexpr int kWavesMulti = 8;        // waves of a workgroup that walks several lists, one after the other
+constexpr int kMultiTilesPerWave = 8; // chunk_rows <= kMultiTilesPerWave * kWavesMulti * kTile there
 constexpr float kLazyStepS = 8.0f;
 constexpr int kMaxTilesPerWave = 16;  // chunk_rows <= kMaxTilesPerWave * kWaves * kTile
 #ifndef DLLM_SPARSE_DEPTH
@@ -36,8 +43,12 @@ struct ChunkGeom {
 };
 __device__ __forceinline__ ChunkGeom chunk_geom(int kb, int chunk_rows) {
   ChunkGeom g;
-  g.n = (kb + chunk_rows - 1) / chunk_rows;
-  g.rows = g.n <= 1 ? chunk_rows : ((kb + g.n - 1) / g.n + 127) / 128 * 128;
+  g.n = 1;
+  g.rows = chunk_rows;
+  if (kb > chunk_rows) {
+    g.n = int(uint32_t(kb + chunk_rows - 1) / uint32_t(chunk_rows));
+    g.rows = int((uint32_t(kb + g.n - 1) / uint32_t(g.n) + 127u) / 128u * 128u);
+  }
   return g;
 }
 
@@ -47,11 +58,37 @@ struct SeqInfo {
   int b, ko0, kb, q0, nq, kv0;
 };
 
-// Sequence handled by grid slot z.  With `ranked` set (small batches whose workgroups do not all fit
-// on the chip at once) sequences are taken in descending order of kept rows (ties: lower sequence
-// first), so the longest lists start first and the short ones fill the compute units that free up;
-// every workgroup derives the same order from cu_k.
-__device__ __forceinline__ SeqInfo sequence_of_slot(const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv,
+// The batch's offsets as one workgroup holds them: lane i holds sequence i's entries and its rank in
+// descending order of kept rows (ties: lower sequence first); every workgroup derives the same order
+// from cu_k.  Batches of more than kRankBatch sequences are not ranked and read their entries per use.
+struct BatchInfo {
+  int ko0, kb, q0, nq, kv0, rank;
+};
+__device__ __forceinline__ BatchInfo load_batch(const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv,
+                                                const int32_t* __restrict__ cu_k, int batch, int lane, bool ranked) {
+  BatchInfo bi = {0, 0, 0, 0, 0, 0};
+  if (batch > kRankBatch) return bi;
+  const int i = lane < batch ? lane : batch - 1;
+  bi.ko0 = cu_k[i]; bi.kb = cu_k[i + 1] - bi.ko0;
+  bi.q0 = cu_q[i]; bi.nq = cu_q[i + 1] - bi.q0;
+  bi.kv0 = cu_kv[i];
+  if (ranked) {
+    const int mine = lane < batch ? bi.kb : -1;
+    int rank = 0;
+    for (int j = 0; j < batch; ++j) {
+      const int other = __builtin_amdgcn_readlane(mine, j);
+      rank += (other > mine) || (other == mine && j < lane);
+    }
+    bi.rank = rank;
+  }
+  return bi;
+}
+
+// Sequence handled by slot z.  With `ranked` set (small batches whose workgroups do not all fit on the
+// chip at once, or that are shared out by length) it is the z-th in descending order of kept rows, so
+// the longest lists start first and the short ones fill the compute units that free up.
+__device__ __forceinline__ SeqInfo sequence_of_slot(const BatchInfo& bi, const int32_t* __restrict__ cu_q,
+                                                    const int32_t* __restrict__ cu_kv,
                                                     const int32_t* __restrict__ cu_k, int batch, int z, int lane,
                                                     bool ranked) {
   SeqInfo si;
@@ -62,27 +99,98 @@ __device__ __forceinline__ SeqInfo sequence_of_slot(const int32_t* __restrict__ 
     si.kv0 = cu_kv[z];
     return si;
   }
-  const int i = lane < batch ? lane : batch - 1;
-  const int ko0 = cu_k[i], kb = cu_k[i + 1] - ko0;
-  const int q0 = cu_q[i], nq = cu_q[i + 1] - q0;
-  const int kv0 = cu_kv[i];
   int b = z;
-  if (ranked) {
-    const int mine = lane < batch ? kb : -1;
-    int rank = 0;
-    for (int j = 0; j < batch; ++j) {
-      const int other = __builtin_amdgcn_readlane(mine, j);
-      rank += (other > mine) || (other == mine && j < lane);
-    }
-    b = __builtin_ctzll(__builtin_amdgcn_ballot_w64(lane < batch && rank == z));
-  }
+  if (ranked) b = __builtin_ctzll(__builtin_amdgcn_ballot_w64(lane < batch && bi.rank == z));
   si.b = b;
-  si.ko0 = __builtin_amdgcn_readlane(ko0, b);
-  si.kb = __builtin_amdgcn_readlane(kb, b);
-  si.q0 = __builtin_amdgcn_readlane(q0, b);
-  si.nq = __builtin_amdgcn_readlane(nq, b);
-  si.kv0 = __builtin_amdgcn_readlane(kv0, b);
+  si.ko0 = __builtin_amdgcn_readlane(bi.ko0, b);
+  si.kb = __builtin_amdgcn_readlane(bi.kb, b);
+  si.q0 = __builtin_amdgcn_readlane(bi.q0, b);
+  si.nq = __builtin_amdgcn_readlane(bi.nq, b);
+  si.kv0 = __builtin_amdgcn_readlane(bi.kv0, b);
   return si;
+}
+__device__ __forceinline__ SeqInfo sequence_of_slot(const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv,
+                                                    const int32_t* __restrict__ cu_k, int batch, int z, int lane,
+                                                    bool ranked) {
+  return sequence_of_slot(load_batch(cu_q, cu_kv, cu_k, batch, lane, ranked), cu_q, cu_kv, cu_k, batch, z, lane,
+                          ranked);
+}
+
+// One 32-key tile that lies in LDS (K rows in ktile, V rows in vtile, the 32 queries in qtile, all in the
+// swizzled tile layout): S^T = K Q^T, online softmax over the first nvalid keys, O^T += V^T P^T.
+template <int D>
+__device__ __forceinline__ void sparse_tile_math(const char* ktile, const char* vtile, const char* qtile,
+                                                 const KAddr<D>& ka, const VtAddr<D>& vt, int hf, int nvalid,
+                                                 float zscale, float& m_used, float& lsum, f32x16 (&acc)[D / 32]) {
+  constexpr int ROWB = 2 * D;
+  constexpr int NT = D / 16;    // MFMA steps along head_dim
+  constexpr int NDB = D / 32;   // 32-wide blocks of head_dim in the output
+  // S^T tile: rows = keys, columns = queries
+  f32x16 st;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) st[i] = 0.0f;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+    st = mfma_bf16(*reinterpret_cast<const v4u*>(ktile + ka.off(t)),
+                   *reinterpret_cast<const v4u*>(qtile + ka.off(t)), st);
+  // issue order: operand fetches just ahead of their MFMA, so few operand registers are live
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  if (nvalid < kTile) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = 8 * (i / 4) + 4 * hf + (i % 4);
+      if (key >= nvalid) st[i] = -INFINITY;
+    }
+  }
+  float tmax = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, st[i]), st[i + 1]);
+  tmax = max_across_halves(tmax) * zscale;   // zscale >= 0
+  if (__builtin_amdgcn_ballot_w64(tmax > m_used + kLazyStepS) != 0) {
+    const float m_new = fmaxf(m_used, tmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_used - m_new);   // first tile: exp2(-inf) = 0
+    m_used = m_new;
+    lsum *= alpha;
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
+  }
+  const float neg_m = -m_used;
+  v4u pb[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    uint32_t w[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * jj], zscale, neg_m));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * jj + 1], zscale, neg_m));
+      w[jj] = cvt_pk_bf16(p0, p1);
+      lsum = add_pair_bf16(w[jj], lsum);
+    }
+    pb[u] = v4u{w[0], w[1], w[2], w[3]};
+  }
+  // O^T += V^T P^T, 16 keys per step
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) {
+      const v2u lo = lds_read_tr16(vtile + vt.off(0, db) + 16 * u * ROWB);
+      const v2u hi = lds_read_tr16(vtile + vt.off(1, db) + 16 * u * ROWB);
+      acc[db] = mfma_bf16(v4u{lo.x, lo.y, hi.x, hi.y}, pb[u], acc[db]);
+    }
+#pragma unroll
+  for (int i = 0; i < 2 * NDB; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+  }
 }
 
 template <int D>
@@ -96,7 +204,6 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = kTile * ROWB;
   constexpr int NLD = kTile * CH / 64;  // 16-byte loads per lane per tile and tensor
-  constexpr int NT = D / 16;            // MFMA steps along head_dim
   constexpr int NDB = D / 32;           // 32-wide blocks of head_dim in the output
 
   // per wave: K tile then V tile; reused as fp32 merge space afterwards
@@ -108,6 +215,15 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int col = lane & 31, hf = lane >> 5;
+  // Every kernel argument is fetched now, next to the loads of the batch's offsets, and not where it
+  // is first used: the gathers cannot start before the last of them has arrived.
+  {
+    auto fetch_now = [](auto x) { asm volatile("" ::"s"(x)); };
+    fetch_now(q); fetch_now(k); fetch_now(v); fetch_now(idx); fetch_now(seq_mode); fetch_now(o);
+    fetch_now(total_k); fetch_now(chunk_rows); fetch_now(ranked);
+    fetch_now(s.batch); fetch_now(s.hq); fetch_now(s.group); fetch_now(s.q_tok); fetch_now(s.q_head);
+    fetch_now(s.kv_tok); fetch_now(s.kv_head); fetch_now(s.total_q); fetch_now(s.scale);
+  }
   const int chunk = blockIdx.x, h = blockIdx.y;
   const SeqInfo si = sequence_of_slot(cu_q, cu_kv, cu_k, s.batch, blockIdx.z, lane, ranked != 0);
   const int b = si.b;
@@ -209,73 +325,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-      // S^T tile: rows = keys, columns = queries
-      f32x16 st;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) st[i] = 0.0f;
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-        st = mfma_bf16(*reinterpret_cast<const v4u*>(ktile + kar.off(t)),
-                       *reinterpret_cast<const v4u*>(qtile + kar.off(t)), st);
-      // issue order: operand fetches just ahead of their MFMA, so few operand registers are live
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-
-      const int nvalid = c1 - (c0 + tile * kTile);
-      if (nvalid < kTile) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = 8 * (i / 4) + 4 * hf + (i % 4);
-          if (key >= nvalid) st[i] = -INFINITY;
-        }
-      }
-      float tmax = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, st[i]), st[i + 1]);
-      tmax = max_across_halves(tmax) * zscale;   // zscale >= 0
-      if (__builtin_amdgcn_ballot_w64(tmax > m_used + kLazyStepS) != 0) {
-        const float m_new = fmaxf(m_used, tmax);
-        const float alpha = __builtin_amdgcn_exp2f(m_used - m_new);   // first tile: exp2(-inf) = 0
-        m_used = m_new;
-        lsum *= alpha;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[db][i] *= alpha;
-      }
-      const float neg_m = -m_used;
-      v4u pb[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        uint32_t w[4];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * jj], zscale, neg_m));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[8 * u + 2 * jj + 1], zscale, neg_m));
-          w[jj] = cvt_pk_bf16(p0, p1);
-          lsum = add_pair_bf16(w[jj], lsum);
-        }
-        pb[u] = v4u{w[0], w[1], w[2], w[3]};
-      }
-      // O^T += V^T P^T, 16 keys per step
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-          const v2u lo = lds_read_tr16(vtile + vtr.off(0, db) + 16 * u * ROWB);
-          const v2u hi = lds_read_tr16(vtile + vtr.off(1, db) + 16 * u * ROWB);
-          acc[db] = mfma_bf16(v4u{lo.x, lo.y, hi.x, hi.y}, pb[u], acc[db]);
-        }
-#pragma unroll
-      for (int i = 0; i < 2 * NDB; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      }
+      sparse_tile_math<D>(ktile, vtile, qtile, kar, vtr, hf, c1 - (c0 + tile * kTile), zscale, m_used, lsum, acc);
       __builtin_amdgcn_wave_barrier();
     };
 
@@ -369,6 +419,252 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
   }
 }
 
+// The same computation for batches with more lists than compute units and lists of unequal length.
+// A one-dimensional grid of one eight-wave workgroup per compute unit shares out all (sequence, head,
+// chunk) items, sequences sorted by descending number of kept rows, in serpentine order (item i of turn
+// r goes to workgroup i or gridDim.x - 1 - i), so that every workgroup walks about the same number of kept
+// rows; a workgroup walks its items shortest first, each with all its waves (a "pass" is one query
+// tile of one item).  Passes are pipelined: while one is walked, the queries and the kept-row ids of
+// the next go from global memory straight into a second pair of LDS buffers, and a wave's last round
+// already gathers its first tile of the next pass, so that those rows are in flight while the waves
+// merge.  LDS holds the eight waves' tiles, two query tiles and two sets of ids: 160 KB at D = 128.
+template <int D>
+__global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ idx,
+    const int32_t* __restrict__ cu_k, int32_t total_k, const uint8_t* __restrict__ seq_mode,
+    uint16_t* __restrict__ o, float* __restrict__ po, float* __restrict__ pm, float* __restrict__ pl,
+    int32_t chunk_rows, int32_t n_chunks, int32_t n_wg, Shape s) {
+  constexpr int WAVES = kWavesMulti;   // n_wg: the size of the grid, as an argument like the others
+  constexpr int CH = D / 8;
+  constexpr int ROWB = 2 * D;
+  constexpr int TILEB = kTile * ROWB;
+  constexpr int NLD = kTile * CH / 64;
+  constexpr int NDB = D / 32;
+  constexpr int kIds = kMultiTilesPerWave * kTile;   // ids per wave and pass
+
+  __shared__ __attribute__((aligned(16))) char lds[WAVES][2 * TILEB];   // per wave: K tile, V tile; merge space
+  __shared__ __attribute__((aligned(16))) char qtile[2][TILEB];          // queries of the current and the next pass
+  __shared__ __attribute__((aligned(16))) int sm_rows[2][WAVES][kIds];   // kept-row ids of both; (m, l) at the merge
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  // Every kernel argument is fetched now, next to the loads of the batch's offsets, and not where it
+  // is first used: the first pass cannot start before the last of them has arrived.
+  {
+    auto fetch_now = [](auto x) { asm volatile("" ::"s"(x)); };
+    fetch_now(q); fetch_now(k); fetch_now(v); fetch_now(idx); fetch_now(seq_mode); fetch_now(o);
+    fetch_now(total_k); fetch_now(chunk_rows); fetch_now(n_chunks); fetch_now(n_wg);
+    fetch_now(s.batch); fetch_now(s.hq); fetch_now(s.group); fetch_now(s.q_tok); fetch_now(s.q_head);
+    fetch_now(s.kv_tok); fetch_now(s.kv_head); fetch_now(s.total_q); fetch_now(s.scale);
+  }
+  const BatchInfo bi = load_batch(cu_q, cu_kv, cu_k, s.batch, lane, true);
+  const int n_items = n_chunks * s.hq * s.batch;
+  const uint32_t pitch = uint32_t(s.kv_tok) * 2u;
+  const float zscale = s.scale * kLog2e;
+
+  struct Pass {
+    int h, chunk, qt, q0, nq, c0, c1, nch, ntiles;
+    const int32_t* rows;
+    const char *kbase, *vbase;
+  };
+  // the next pass of this workgroup: the next query tile of the item, else the next item that has work
+  int turn = (n_items + n_wg - 1) / n_wg;
+  auto next_pass = [&](Pass& p, bool have) -> bool {
+    if (have && (p.qt + 1) * 32 < p.nq) {
+      ++p.qt;
+      return true;
+    }
+    while (--turn >= 0) {
+      const int item = turn * n_wg + ((turn & 1) ? n_wg - 1 - int(blockIdx.x) : int(blockIdx.x));
+      if (item >= n_items) continue;
+      // (unsigned divisions, and none by n_chunks when every list is one chunk: this runs before the
+      // first load of a pass can be issued)
+      const uint32_t pair = n_chunks == 1 ? uint32_t(item) : uint32_t(item) / uint32_t(n_chunks);
+      const int chunk = n_chunks == 1 ? 0 : int(uint32_t(item) - pair * uint32_t(n_chunks));
+      const int z = int(pair / uint32_t(s.hq)), h = int(pair - uint32_t(z) * uint32_t(s.hq));
+      const SeqInfo si = sequence_of_slot(bi, cu_q, cu_kv, cu_k, s.batch, z, lane, true);
+      if (seq_mode != nullptr && seq_mode[si.b] == DLLM_SEQ_DENSE) continue;
+      const ChunkGeom cg = chunk_geom(si.kb, chunk_rows);
+      const int c0 = chunk * cg.rows;
+      if (c0 >= si.kb && !(chunk == 0 && si.kb == 0)) continue;
+      if (si.kb == 0) {   // nothing kept: defined as zeros
+        for (int e = threadIdx.x; e < si.nq * D; e += WAVES * 64)
+          o[(int64_t(si.q0 + e / D) * s.hq + h) * D + e % D] = 0;
+        continue;
+      }
+      if (si.nq == 0) continue;
+      const int g = h / s.group;
+      p.h = h; p.chunk = chunk; p.qt = 0; p.q0 = si.q0; p.nq = si.nq;
+      p.c0 = c0; p.c1 = min(si.kb, c0 + cg.rows); p.nch = cg.n;
+      p.ntiles = (p.c1 - p.c0 + kTile - 1) / kTile;
+      p.rows = idx + int64_t(h) * total_k + si.ko0;
+      p.kbase = reinterpret_cast<const char*>(k + int64_t(si.kv0) * s.kv_tok + int64_t(g) * s.kv_head);
+      p.vbase = reinterpret_cast<const char*>(v + int64_t(si.kv0) * s.kv_tok + int64_t(g) * s.kv_head);
+      return true;
+    }
+    return false;
+  };
+  // queries and this wave's kept-row ids of pass p -> LDS buffers bf, without passing through registers
+  // (positions past the end repeat the last kept row, rows past the last query repeat the last query:
+  // such rows are masked out of the softmax, such columns are never stored)
+  auto prefetch = [&](const Pass& p, int bf) {
+#pragma unroll
+    for (int j = 0; j < kIds / 64; ++j) {
+      const int slot = j * 64 + lane;
+      const int t = min(p.c0 + (wave + (slot >> 5) * WAVES) * kTile + (slot & 31), p.c1 - 1);
+      if (idx != nullptr)
+        load4_to_lds(p.rows + t, __builtin_amdgcn_readfirstlane(lds_addr(&sm_rows[bf][wave][j * 64])));
+      else sm_rows[bf][wave][slot] = t;   // NULL idx: identity lists (a packed cache)
+    }
+    if (kTile * CH >= WAVES * 64 || threadIdx.x < kTile * CH) {
+      const int r = threadIdx.x / CH, c = (threadIdx.x % CH) ^ tile_swz<D>(r);
+      const int qi = min(p.qt * 32 + r, p.nq - 1);
+      load16_to_lds(q + int64_t(p.q0 + qi) * s.q_tok + int64_t(p.h) * s.q_head + c * 8,
+                    __builtin_amdgcn_readfirstlane(lds_addr(qtile[bf]) + wave * 1024));
+    }
+  };
+  static_assert(kTile * CH <= WAVES * 64, "one 16-byte query chunk per thread");
+
+  char* ktile = lds[wave];
+  char* vtile = lds[wave] + TILEB;
+  KAddr<D> ka;
+  ka.init(lane);
+  VtAddr<D> vt;
+  vt.init(lane);
+  const uint32_t coff = (lane % CH) * 16;
+  auto opaque = [](int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+  };
+  // gather tile j of this wave in pass p
+  auto fetch = [&](v4u (&kr)[NLD], v4u (&vr)[NLD], const Pass& p, int bf, int j) {
+    const int* my_rows = sm_rows[bf][wave];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const uint32_t off = __umul24(uint32_t(my_rows[j * kTile + (i * 64 + lane) / CH]), pitch) + coff;
+      kr[i] = load_once(p.kbase + off);
+      vr[i] = load_once(p.vbase + off);
+    }
+  };
+
+  Pass cur, nxt;
+  if (!next_pass(cur, false)) return;
+  int bf = 0;
+  prefetch(cur, 0);
+  wait_tile_loads();
+  v4u kra[NLD], vra[NLD];
+  if (wave < cur.ntiles) fetch(kra, vra, cur, 0, 0);
+  __syncthreads();   // the queries are in place
+  for (;;) {
+    nxt = cur;
+    const bool more = next_pass(nxt, true);
+    if (more) prefetch(nxt, bf ^ 1);
+    // what a wave does once its own tiles of this pass are on their way: its first tile of the next
+    auto start_next = [&]() {
+      if (more) {
+        wait_tile_loads();   // the next pass's ids (nothing else is outstanding here)
+        if (wave < nxt.ntiles) fetch(kra, vra, nxt, bf ^ 1, 0);
+      }
+    };
+    float m_used = -INFINITY, lsum = 0.0f;
+    f32x16 acc[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[db][i] = 0.0f;
+    if (wave >= cur.ntiles) start_next();
+    for (int j = 0, tile = wave; tile < cur.ntiles; ++j, tile += WAVES) {
+      KAddr<D> kar;
+      kar.base = opaque(ka.base);
+      VtAddr<D> vtr;
+      vtr.base[0] = opaque(vt.base[0]);
+      vtr.base[1] = opaque(vt.base[1]);
+      const int lane_o = opaque(lane);
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int f = i * 64 + lane_o, woff = tile_off<D>(f / CH, f % CH);
+        *reinterpret_cast<v4u*>(ktile + woff) = kra[i];
+        *reinterpret_cast<v4u*>(vtile + woff) = vra[i];
+      }
+      if (tile + WAVES < cur.ntiles) fetch(kra, vra, cur, bf, j + 1);
+      else start_next();
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      sparse_tile_math<D>(ktile, vtile, qtile[bf], kar, vtr, hf, cur.c1 - (cur.c0 + tile * kTile), zscale, m_used,
+                          lsum, acc);
+      __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- merge the eight waves' (m, l, O^T) through LDS (see attend_sparse_bf16_kernel)
+    const float l = sum_across_halves(lsum);
+    float* sm_ml = reinterpret_cast<float*>(&sm_rows[bf][0][0]);   // [wave][m: 32 | l: 32]
+    if (hf == 0) {
+      sm_ml[wave * kIds + col] = m_used;
+      sm_ml[wave * kIds + 32 + col] = l;
+    }
+    float4* mrg = reinterpret_cast<float4*>(&lds[0][0]);
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4)
+        mrg[((wave * NDB + db) * 4 + i4) * 64 + lane] =
+            make_float4(acc[db][4 * i4 + 0], acc[db][4 * i4 + 1], acc[db][4 * i4 + 2], acc[db][4 * i4 + 3]);
+    __syncthreads();
+    if (wave < NDB) {
+      const int db = wave;
+      float m_all = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) m_all = fmaxf(m_all, sm_ml[w * kIds + col]);
+      float f[WAVES];
+      float l_all = 0.0f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) {
+        f[w] = __builtin_amdgcn_exp2f(sm_ml[w * kIds + col] - m_all);   // 0 for a wave that saw no tile
+        l_all += sm_ml[w * kIds + 32 + col] * f[w];
+      }
+      float outv[16];
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+          const float4 x = mrg[((w * NDB + db) * 4 + i4) * 64 + lane];
+          a.x += x.x * f[w]; a.y += x.y * f[w]; a.z += x.z * f[w]; a.w += x.w * f[w];
+        }
+        outv[4 * i4 + 0] = a.x; outv[4 * i4 + 1] = a.y; outv[4 * i4 + 2] = a.z; outv[4 * i4 + 3] = a.w;
+      }
+      const int qi = cur.qt * 32 + col;
+      if (qi < cur.nq) {
+        if (cur.nch == 1) {
+          const float inv = 1.0f / l_all;
+          uint16_t* op = o + (int64_t(cur.q0 + qi) * s.hq + cur.h) * D + db * 32 + 4 * hf;
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            v2u w2;
+            w2.x = cvt_pk_bf16(outv[4 * i4 + 0] * inv, outv[4 * i4 + 1] * inv);
+            w2.y = cvt_pk_bf16(outv[4 * i4 + 2] * inv, outv[4 * i4 + 3] * inv);
+            *reinterpret_cast<v2u*>(op + 8 * i4) = w2;
+          }
+        } else {
+          const int64_t slot = (int64_t(cur.chunk) * s.total_q + (cur.q0 + qi)) * s.hq + cur.h;
+          float* pp = po + slot * D + db * 32 + 4 * hf;
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4)
+            *reinterpret_cast<float4*>(pp + 8 * i4) =
+                make_float4(outv[4 * i4 + 0], outv[4 * i4 + 1], outv[4 * i4 + 2], outv[4 * i4 + 3]);
+          if (db == 0 && hf == 0) { pm[slot] = m_all; pl[slot] = l_all; }
+        }
+      }
+    }
+    if (!more) break;
+    __syncthreads();   // merge space becomes tile space again; the next pass's queries are in place
+    cur = nxt;
+    bf ^= 1;
+  }
+}
+
 // Merge the chunk partials of every (sequence, head) that needed more than one chunk.
 // One workgroup per (head, sequence): 8 threads per query row, each owning D/8 output elements,
 // so all loads of a row are independent and issued together.
@@ -422,16 +718,36 @@ hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const 
   const uint16_t *qh = static_cast<const uint16_t*>(q), *kh = static_cast<const uint16_t*>(k),
                  *vh = static_cast<const uint16_t*>(v);
   uint16_t* oh = static_cast<uint16_t*>(o);
-  dim3 grid(p.n_chunks, s.hq, s.batch);
-  // the start order only matters when the workgroups cannot all be resident at once (two per compute unit)
-  const int ranked = int64_t(p.n_chunks) * s.hq * s.batch > 512 ? 1 : 0;
-  if (s.d == 128)
-    attend_sparse_bf16_kernel<128><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
-                                                                seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
-  else
-    attend_sparse_bf16_kernel<64><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
-                                                               seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
-  hipError_t e = hipGetLastError();
+  // More lists than compute units, and lists of unequal length (the longest at least 1.5 times the mean
+  // over the batch): one eight-wave workgroup per compute unit walks its share of them.  With lists of
+  // equal length one list per workgroup is faster (40 against 44 us on the mixed workload's Reuse part).
+  int dev = 0, n_cu = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  const int64_t n_items = int64_t(p.n_chunks) * s.hq * s.batch;
+  const bool multi = n_items > n_cu && n_items < (int64_t(1) << 30) &&
+                     p.chunk_rows <= kMultiTilesPerWave * kWavesMulti * kTile &&
+                     2 * int64_t(p.max_k) * s.batch >= 3 * int64_t(total_k);
+  if (multi) {
+    if (s.d == 128)
+      attend_sparse_multi_bf16_kernel<128><<<n_cu, kWavesMulti * 64, 0, st>>>(
+          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s);
+    else
+      attend_sparse_multi_bf16_kernel<64><<<n_cu, kWavesMulti * 64, 0, st>>>(
+          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s);
+  } else {
+    dim3 grid(p.n_chunks, s.hq, s.batch);
+    // the start order only matters when the workgroups cannot all be resident at once (two per compute unit)
+    const int ranked = n_items > 512 ? 1 : 0;
+    if (s.d == 128)
+      attend_sparse_bf16_kernel<128><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
+                                                                  seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
+    else
+      attend_sparse_bf16_kernel<64><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
+                                                                 seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
+  }
+  e = hipGetLastError();
   if (e != hipSuccess || p.n_chunks <= 1) return e;
   dim3 cgrid(s.hq, s.batch);
   if (s.d == 128)

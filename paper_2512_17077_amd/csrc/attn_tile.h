@@ -107,7 +107,17 @@ __device__ __forceinline__ void load16_to_lds(const void* uniform_base, uint32_t
       : "v"(lane_off), "s"(uniform_base), "s"(lds_wave_base)
       : "memory");
 }
-// Waits until every load16_to_lds this wave has issued has written its LDS bytes.
+// Four bytes per lane: lane l's dword lands at LDS byte address lds_wave_base + 4 * l.
+__device__ __forceinline__ void load4_to_lds(const void* src, uint32_t lds_wave_base) {
+  asm volatile(
+      "s_mov_b32 m0, %1\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %0, off"
+      :
+      : "v"(src), "s"(lds_wave_base)
+      : "memory");
+}
+// Waits until every load16_to_lds / load4_to_lds this wave has issued has written its LDS bytes.
 __device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // LDS byte address of a pointer into a __shared__ array

@@ -43,6 +43,7 @@ hipError_t launch_pack(const Shape& s, dllm_dtype dt, const void* k, const void*
 struct AttendPlan {
   int32_t chunk_rows;  // kept rows one workgroup walks
   int32_t n_chunks;    // upper bound on chunks per (sequence, head)
+  int32_t max_k;       // the caller's bound on kept rows per (sequence, head)
   size_t off_po, off_pm, off_pl, bytes;
 };
 AttendPlan plan_attend(const Shape& s, dllm_dtype dt, int32_t max_k);

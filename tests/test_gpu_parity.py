@@ -223,6 +223,28 @@ def test_attend_chunked_long_keep_lists():
     check_attend(w2, oracle_select(w2))
 
 
+@pytest.mark.parametrize("D", [128, 64])
+def test_attend_more_lists_than_compute_units(D):
+    """More (sequence, head, chunk) items than compute units: each workgroup walks several of them."""
+    lens = [900, 40, 300, 65, 700, 129, 77, 512, 33, 260, 1000, 90]
+    keep = [800, 1, 33, 65, 517, 0, 77, 0, 32, 129, 31, 90]        # nothing kept, single rows, ragged tails
+    qlens = [32, 1, 7, 33, 32, 32, 70, 32, 0, 32, 32, 5]           # one and three query tiles, no query
+    mode = np.array([0, 0, 0, 0, 0, 0, 0, 1, 0, 0, 0, 0], np.uint8)  # one sequence is left to the dense path
+    w = custom(12, torch.bfloat16, 32, 8, D, lens, qlens, keep, mode=mode)
+    check_attend(w, oracle_select(w))
+    # long lists cut into chunks: 3 sequences x 32 heads x 3 chunks
+    w2 = custom(13, torch.bfloat16, 32, 32, D, [5000, 2500, 100], [32, 9, 32], [4500, 2100, 7])
+    dw = hcsa.DeviceWorkload(w2)
+    assert hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k) > 0
+    check_attend(w2, oracle_select(w2), dw=dw)
+    # more than 64 sequences (walked in batch order)
+    rng = np.random.default_rng(14)
+    lens3 = rng.integers(20, 200, size=70).tolist()
+    keep3 = [int(rng.integers(0, l + 1)) for l in lens3]
+    w3 = custom(14, torch.bfloat16, 8, 2, D, lens3, [32] * 70, keep3)
+    check_attend(w3, oracle_select(w3))
+
+
 def test_attend_keep_all_equals_dense_entry_point():
     w = custom(11, torch.bfloat16, 4, 2, 128, [333, 64], [32, 20], [333, 64])
     idx = oracle_select(w)
