@@ -612,8 +612,11 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
         mrg[((wave * NDB + db) * 4 + i4) * 64 + lane] =
             make_float4(acc[db][4 * i4 + 0], acc[db][4 * i4 + 1], acc[db][4 * i4 + 2], acc[db][4 * i4 + 3]);
     __syncthreads();
-    if (wave < NDB) {
-      const int db = wave;
+    {
+      // every wave reduces a quarter or an eighth of the tile: head_dim block db, register quads i4_0 ...
+      constexpr int PARTS = WAVES / NDB, NQ4 = 4 / PARTS;
+      static_assert(WAVES % NDB == 0 && 4 % PARTS == 0, "the waves split the output evenly");
+      const int db = wave % NDB, i4_0 = (wave / NDB) * NQ4;
       float m_all = -INFINITY;
 #pragma unroll
       for (int w = 0; w < WAVES; ++w) m_all = fmaxf(m_all, sm_ml[w * kIds + col]);
@@ -624,16 +627,16 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
         f[w] = __builtin_amdgcn_exp2f(sm_ml[w * kIds + col] - m_all);   // 0 for a wave that saw no tile
         l_all += sm_ml[w * kIds + 32 + col] * f[w];
       }
-      float outv[16];
+      float outv[4 * NQ4];
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
+      for (int n = 0; n < NQ4; ++n) {
         float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) {
-          const float4 x = mrg[((w * NDB + db) * 4 + i4) * 64 + lane];
+          const float4 x = mrg[((w * NDB + db) * 4 + i4_0 + n) * 64 + lane];
           a.x += x.x * f[w]; a.y += x.y * f[w]; a.z += x.z * f[w]; a.w += x.w * f[w];
         }
-        outv[4 * i4 + 0] = a.x; outv[4 * i4 + 1] = a.y; outv[4 * i4 + 2] = a.z; outv[4 * i4 + 3] = a.w;
+        outv[4 * n + 0] = a.x; outv[4 * n + 1] = a.y; outv[4 * n + 2] = a.z; outv[4 * n + 3] = a.w;
       }
       const int qi = cur.qt * 32 + col;
       if (qi < cur.nq) {
@@ -641,20 +644,20 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
           const float inv = 1.0f / l_all;
           uint16_t* op = o + (int64_t(cur.q0 + qi) * s.hq + cur.h) * D + db * 32 + 4 * hf;
 #pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) {
+          for (int n = 0; n < NQ4; ++n) {
             v2u w2;
-            w2.x = cvt_pk_bf16(outv[4 * i4 + 0] * inv, outv[4 * i4 + 1] * inv);
-            w2.y = cvt_pk_bf16(outv[4 * i4 + 2] * inv, outv[4 * i4 + 3] * inv);
-            *reinterpret_cast<v2u*>(op + 8 * i4) = w2;
+            w2.x = cvt_pk_bf16(outv[4 * n + 0] * inv, outv[4 * n + 1] * inv);
+            w2.y = cvt_pk_bf16(outv[4 * n + 2] * inv, outv[4 * n + 3] * inv);
+            *reinterpret_cast<v2u*>(op + 8 * (i4_0 + n)) = w2;
           }
         } else {
           const int64_t slot = (int64_t(cur.chunk) * s.total_q + (cur.q0 + qi)) * s.hq + cur.h;
           float* pp = po + slot * D + db * 32 + 4 * hf;
 #pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4)
-            *reinterpret_cast<float4*>(pp + 8 * i4) =
-                make_float4(outv[4 * i4 + 0], outv[4 * i4 + 1], outv[4 * i4 + 2], outv[4 * i4 + 3]);
-          if (db == 0 && hf == 0) { pm[slot] = m_all; pl[slot] = l_all; }
+          for (int n = 0; n < NQ4; ++n)
+            *reinterpret_cast<float4*>(pp + 8 * (i4_0 + n)) =
+                make_float4(outv[4 * n + 0], outv[4 * n + 1], outv[4 * n + 2], outv[4 * n + 3]);
+          if (wave == 0 && hf == 0) { pm[slot] = m_all; pl[slot] = l_all; }
         }
       }
     }
