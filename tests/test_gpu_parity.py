@@ -505,12 +505,14 @@ def test_sequences_without_queries():
 
 # ------------------------------------------------------------------ HIP graph capture
 
-def test_select_and_attend_replayed_from_a_hip_graph():
-    """A serving loop captures the launch-bound step (five launches of the layer-shaped config) once and
-    replays it.  The library allocates nothing, clears nothing with memsets and never synchronises, so a
-    captured select + attend must give, on every replay and with eager work in between, exactly what
-    the eager calls give for the inputs then in the buffers (and the oracle's indices)."""
-    w = synth.config(2)
+@pytest.mark.parametrize("which_workload", ["layer-shaped config 2", "ragged batch (config 3 / 4)"])
+def test_select_and_attend_replayed_from_a_hip_graph(which_workload):
+    """A serving loop captures the launch-bound step once and replays it.  The library allocates
+    nothing, clears nothing with memsets and never synchronises, so a captured select + attend must
+    give, on every replay and with eager work in between, exactly what the eager calls give for the
+    inputs then in the buffers (and the oracle's indices).  The ragged batch has more lists than
+    compute units and takes the multi-list attend kernel."""
+    w = synth.config(2) if which_workload.startswith("layer") else synth.config(3, scale_down=4)
     dw = hcsa.DeviceWorkload(w)
     wss = torch.empty(max(256, hcsa.dllm_hcsa_select_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
     wsa = torch.empty(max(256, hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
@@ -528,7 +530,7 @@ def test_select_and_attend_replayed_from_a_hip_graph():
     assert np.array_equal(ref["a"][0].cpu().numpy(), oracle_select(w))
     assert not torch.equal(ref["a"][0], ref["b"][0])
 
-    say("capturing select + attend of config 2")
+    say(f"capturing select + attend of {which_workload}")
     graph = torch.cuda.CUDAGraph()
     dw.q.copy_(q_a)
     torch.cuda.synchronize()
