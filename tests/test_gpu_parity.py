@@ -124,6 +124,23 @@ def test_select_list_lengths_around_4096(pool_w):
     check_select(w2, pool_w=pool_w)
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv,D", [(torch.bfloat16, 32, 8, 128), (torch.bfloat16, 16, 16, 64),
+                                            (torch.float32, 16, 8, 64), (torch.bfloat16, 24, 8, 128)])
+def test_select_large_ragged_batches(dtype, Hq, Hkv, D):
+    """Half a million (token, KV head) rows: ragged lengths around the 16- and 64-row tile sizes,
+    sequences that are not scored, one to four query heads per KV head."""
+    per_head = 2048 * 256 // Hkv
+    lens = [1, 15, 16, 17, 63, 300, 4097, 8192, 31]
+    keep = [1, 0, 16, 5, 0, 150, 2000, 4096, 31]
+    qlens = [32, 32, 1, 7, 32, 33, 32, 32, 32]
+    while sum(lens) < per_head + 64:                  # fill up with long sequences
+        lens.append(min(20001, per_head + 64 - sum(lens)))
+        keep.append(lens[-1] // 3)
+        qlens.append(32)
+    w = custom(15, dtype, Hq, Hkv, D, lens, qlens, keep, salient=0.02)
+    check_select(w)
+
+
 def test_select_strided_inputs():
     """q/k/v as views into one fused QKV activation, the layout a model layer would hand over."""
     Hq, Hkv, D, L = 8, 2, 128, 777
