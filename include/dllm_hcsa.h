@@ -96,7 +96,7 @@ typedef struct {
  * written ascending by position into idx_out (layout above).  Sequences with k_b == 0 are skipped.
  *
  * pool_w must be odd and between 1 and 63.  max_k bounds k_b; 1 <= max_k <= max_kv.
- * max_kv may not exceed 32768 (one sequence's scores are ranked inside one compute unit's LDS).
+ * max_kv may not exceed 32768 (one sequence's scores are ranked by one workgroup, inside one compute unit).
  * Returns DLLM_ERR_WORKSPACE if workspace_bytes < dllm_hcsa_select_workspace(batch, max_k).
  */
 size_t dllm_hcsa_select_workspace(const dllm_batch *batch, int32_t max_k);
