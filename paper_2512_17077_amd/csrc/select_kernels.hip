@@ -668,7 +668,7 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
   if (s.max_kv <= 8 * kTopkThreads) {
     // Keys in registers.  (Sixteen keys per thread for lists of up to 8192 measured slower than the
     // kernel below on the mixed workload, 20.5 against 18.1 us, although each workgroup took less time:
-    // a compute unit held fewer of them at once.  Thirty-two per thread in four waves took 25 us.)
+    // they did not all run at once.  Thirty-two per thread in four waves took 25 us.)
     topk_reg_kernel<8, kTopkThreads><<<grid, kTopkThreads, pool_w == 1 ? 0 : size_t(lpad) * 4, st>>>(
         ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, forced_tail, head_sum, s.hq, idx_out);
     return hipGetLastError();
