@@ -130,6 +130,33 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch *batch,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Selection for callers that cannot allocate or hand over device scratch memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and
+ * same argument checks as dllm_hcsa_select_ex, but there is no workspace argument: the fp32 scores
+ * (and the row of head sums) live in a buffer of DLLM_SELECT_STATIC_BYTES that is part of the
+ * library's device image, one copy per GPU, held until the process ends.  The call allocates and
+ * frees nothing (no hipMalloc, no hipFree, no allocating library routine).
+ *   Limit     dllm_hcsa_select_workspace(batch, max_k) must not exceed DLLM_SELECT_STATIC_BYTES
+ *             (about n_q_heads * total_kv * 4 bytes); larger batches get DLLM_ERR_WORKSPACE and
+ *             nothing is launched.
+ *   Device    The buffer used is that of the device that is current when the call is made, which
+ *             must be the device of hip_stream and of every pointer.  Its address is looked up on
+ *             the first call on a device (DLLM_ERR_DEVICE if that fails).
+ *   Sharing   Every call on a GPU uses that GPU's one buffer, which keeps the previous call's
+ *             contents; the kernels write every score before they read it, so nothing needs
+ *             clearing.  Two such calls that overlap in time on one GPU (different streams, or
+ *             different host threads on different streams) race and give undefined lists; calls
+ *             on one stream are ordered and safe.
+ */
+#define DLLM_SELECT_STATIC_BYTES (32u << 20)
+dllm_status dllm_hcsa_select_static(const dllm_batch *batch,
+                                    const int32_t *cu_k, /* device, [batch+1] */
+                                    int32_t total_k, int32_t max_k, int32_t pool_w,
+                                    int32_t forced_tail, int32_t head_sum,
+                                    int32_t *idx_out,    /* device, [n_q_heads, total_k] */
+                                    void *hip_stream);
+
+/*
  * Attention over kept rows (Section 2.3 Eq. 4 restricted to each head's kept set; Eq. 3 for
  * sequences flagged dense).  For sequence b, head h, query row i:
  *     O[i,h,:] = sum_t softmax_t(softmax_scale * Q[i,h,:].K[r_t, h/G, :]) * V[r_t, h/G, :]

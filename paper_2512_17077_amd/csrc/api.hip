@@ -3,8 +3,15 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "common.h"
+
+// Selection scratch of dllm_hcsa_select_static: part of the device image, so every GPU the library
+// runs on holds its own copy at its own address until the process ends.  In host code the array's name
+// is only a handle for hipGetSymbolAddress; the address that kernels and copies may use is looked up
+// once per device, with that device current, and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[DLLM_SELECT_STATIC_BYTES];
 
 namespace {
 
@@ -113,6 +120,44 @@ dllm_status check_select_scalars(const dllm_batch* b, int32_t max_k, int32_t poo
   return DLLM_OK;
 }
 
+
+// Scalar and pointer checks shared by the selection entry points; fills the kernel-side shape.
+dllm_status check_select_call(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
+                              int32_t pool_w, int32_t forced_tail, int32_t head_sum, const int32_t* idx_out,
+                              dllm::Shape* s) {
+  dllm_status st = check_batch(batch, s);
+  if (st != DLLM_OK) return st;
+  if ((st = check_select_scalars(batch, max_k, pool_w)) != DLLM_OK) return st;
+  if (cu_k == nullptr || idx_out == nullptr) return fail(DLLM_ERR_INVALID_ARG, "cu_k and idx_out must be non-NULL");
+  if (total_k < 1 || max_k > total_k)
+    return fail(DLLM_ERR_INVALID_ARG, "need 1 <= max_k <= total_k (got max_k=%d, total_k=%d)", max_k, total_k);
+  if (forced_tail < 0 || forced_tail > max_k)
+    return fail(DLLM_ERR_INVALID_ARG, "forced_tail %d outside 0..max_k (%d)", forced_tail, max_k);
+  if (head_sum != 0 && head_sum != 1) return fail(DLLM_ERR_INVALID_ARG, "head_sum must be 0 or 1 (got %d)", head_sum);
+  return DLLM_OK;
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+dllm_status scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(DLLM_ERR_DEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(DLLM_ERR_UNSUPPORTED, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr)
+      return fail(DLLM_ERR_DEVICE, "hipGetSymbolAddress(selection scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DLLM_OK;
+}
+
 }  // namespace
 
 namespace dllm {
@@ -164,21 +209,34 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch* batch, const int32_t* cu_k, in
                                 int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out,
                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
   dllm::Shape s;
-  dllm_status st = check_batch(batch, &s);
+  dllm_status st = check_select_call(batch, cu_k, total_k, max_k, pool_w, forced_tail, head_sum, idx_out, &s);
   if (st != DLLM_OK) return st;
-  if ((st = check_select_scalars(batch, max_k, pool_w)) != DLLM_OK) return st;
-  if (cu_k == nullptr || idx_out == nullptr) return fail(DLLM_ERR_INVALID_ARG, "cu_k and idx_out must be non-NULL");
-  if (total_k < 1 || max_k > total_k)
-    return fail(DLLM_ERR_INVALID_ARG, "need 1 <= max_k <= total_k (got max_k=%d, total_k=%d)", max_k, total_k);
-  if (forced_tail < 0 || forced_tail > max_k)
-    return fail(DLLM_ERR_INVALID_ARG, "forced_tail %d outside 0..max_k (%d)", forced_tail, max_k);
-  if (head_sum != 0 && head_sum != 1) return fail(DLLM_ERR_INVALID_ARG, "head_sum must be 0 or 1 (got %d)", head_sum);
   if ((st = check_workspace(workspace, workspace_bytes, dllm::plan_select(s).bytes)) != DLLM_OK) return st;
   g_err[0] = 0;
   return device_result(dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k,
                                            total_k, max_k, pool_w, forced_tail, head_sum, idx_out, workspace,
                                            static_cast<hipStream_t>(hip_stream)),
                        "dllm_hcsa_select");
+}
+
+dllm_status dllm_hcsa_select_static(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
+                                    int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out,
+                                    void* hip_stream) {
+  dllm::Shape s;
+  dllm_status st = check_select_call(batch, cu_k, total_k, max_k, pool_w, forced_tail, head_sum, idx_out, &s);
+  if (st != DLLM_OK) return st;
+  const size_t need = dllm::plan_select(s).bytes;
+  if (need > sizeof scratch)
+    return fail(DLLM_ERR_WORKSPACE,
+                "this batch needs %zu bytes of selection scratch, the built-in buffer holds %zu "
+                "(use dllm_hcsa_select_ex with a workspace)", need, sizeof scratch);
+  void* ws = nullptr;
+  if ((st = scratch_of_current_device(&ws)) != DLLM_OK) return st;
+  g_err[0] = 0;
+  return device_result(dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k,
+                                           total_k, max_k, pool_w, forced_tail, head_sum, idx_out, ws,
+                                           static_cast<hipStream_t>(hip_stream)),
+                       "dllm_hcsa_select_static");
 }
 
 dllm_status dllm_hcsa_select(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,

@@ -25,7 +25,7 @@ DLLM_F32, DLLM_BF16 = 0, 1
 DLLM_SEQ_SPARSE, DLLM_SEQ_DENSE = 0, 1
 
 EXPORTS = [
-    "dllm_hcsa_select_workspace", "dllm_hcsa_select", "dllm_hcsa_select_ex",
+    "dllm_hcsa_select_workspace", "dllm_hcsa_select", "dllm_hcsa_select_ex", "dllm_hcsa_select_static",
     "dllm_hcsa_attend_workspace", "dllm_hcsa_attend",
     "dllm_dense_refresh_attend_workspace", "dllm_dense_refresh_attend",
     "dllm_hcsa_pack",
@@ -83,6 +83,8 @@ def lib() -> ctypes.CDLL:
         L.dllm_hcsa_select.argtypes = [P, vp, i32, i32, i32, vp, vp, sz, vp]
         L.dllm_hcsa_select_ex.restype = ctypes.c_int
         L.dllm_hcsa_select_ex.argtypes = [P, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.dllm_hcsa_select_static.restype = ctypes.c_int
+        L.dllm_hcsa_select_static.argtypes = [P, vp, i32, i32, i32, i32, i32, vp, vp]
         L.dllm_hcsa_attend_workspace.restype = sz
         L.dllm_hcsa_attend_workspace.argtypes = [P, i32]
         L.dllm_hcsa_attend.restype = ctypes.c_int
@@ -173,6 +175,17 @@ def dllm_hcsa_select_ex(batch: DllmBatch, cu_k: torch.Tensor, total_k: int, max_
     _raise(lib().dllm_hcsa_select_ex(ctypes.byref(batch), _ptr(cu_k), int(total_k), int(max_k), int(pool_w),
                                      int(forced_tail), int(bool(head_sum)), _ptr(idx_out), _ptr(workspace), nbytes,
                                      _stream(stream)))
+    return idx_out
+
+
+DLLM_SELECT_STATIC_BYTES = 32 << 20
+
+
+def dllm_hcsa_select_static(batch: DllmBatch, cu_k: torch.Tensor, total_k: int, max_k: int, idx_out: torch.Tensor,
+                            pool_w: int = 1, forced_tail: int = 0, head_sum: bool = False, stream=None) -> torch.Tensor:
+    """dllm_hcsa_select_ex on the library's built-in scratch buffer: no workspace, nothing allocated."""
+    _raise(lib().dllm_hcsa_select_static(ctypes.byref(batch), _ptr(cu_k), int(total_k), int(max_k), int(pool_w),
+                                         int(forced_tail), int(bool(head_sum)), _ptr(idx_out), _stream(stream)))
     return idx_out
 
 

@@ -118,6 +118,55 @@ def test_select_ex_option_checks():
     assert status(head_sum=-1) == hcsa.DLLM_ERR_INVALID_ARG
 
 
+def test_select_static_checks_and_size_limit():
+    """The no-workspace selection makes the same host checks, and refuses batches whose scores do not fit
+    its built-in buffer, before any HIP call."""
+    L = hcsa.lib()
+
+    def status(b, forced_tail=0, head_sum=0, max_k=50, pool_w=1, cu_k=FAKE):
+        return L.dllm_hcsa_select_static(ctypes.byref(b), cu_k, 100, max_k, pool_w, forced_tail, head_sum, FAKE, None)
+
+    b = good_batch()
+    assert status(b, forced_tail=51) == hcsa.DLLM_ERR_INVALID_ARG
+    assert status(b, head_sum=2) == hcsa.DLLM_ERR_INVALID_ARG
+    assert status(b, pool_w=4) == hcsa.DLLM_ERR_INVALID_ARG
+    assert status(b, cu_k=None) == hcsa.DLLM_ERR_INVALID_ARG
+    b.head_dim = 96
+    assert status(b) == hcsa.DLLM_ERR_INVALID_ARG
+    big = good_batch()
+    big.total_kv = 2_000_000            # 8 heads x 2e6 positions x 4 bytes = 64 MB of scores
+    assert L.dllm_hcsa_select_workspace(ctypes.byref(big), 50) > hcsa.DLLM_SELECT_STATIC_BYTES
+    assert status(big) == hcsa.DLLM_ERR_WORKSPACE
+    assert "built-in buffer" in hcsa.last_error()
+    text = open(os.path.join(ROOT, "include", "dllm_hcsa.h")).read()
+    assert re.search(r"#define\s+DLLM_SELECT_STATIC_BYTES\s+\(32u\s*<<\s*20\)", text)
+    assert hcsa.DLLM_SELECT_STATIC_BYTES == 32 << 20
+
+
+def test_static_scratch_is_a_global_symbol_of_the_device_image(tmp_path):
+    """The HIP runtime finds a device variable by name in the code object's dynamic symbol table, and
+    aborts the process if it is not there.  A `static __device__` array that host code names is given
+    global binding by the compiler unless something (e.g. a `used` attribute) keeps it local: check
+    what was built."""
+    import shutil
+    import subprocess
+    llvm = "/opt/rocm/llvm/bin"
+    tools = [os.path.join(llvm, t) for t in ("llvm-objcopy", "clang-offload-bundler", "llvm-readelf")]
+    obj = os.path.join(ROOT, "paper_2512_17077_amd", "_build", "api.o")
+    if not all(os.path.exists(t) for t in tools) or not os.path.exists(obj):
+        pytest.skip("ROCm llvm tools or the build's api.o not present")
+    fat, co = str(tmp_path / "api.fatbin"), str(tmp_path / "api.co")
+    subprocess.run([tools[0], "-O", "binary", "--only-section=.hip_fatbin", obj, fat], check=True)
+    subprocess.run([tools[1], "--unbundle", "--type=o", f"--input={fat}",
+                    "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={co}"], check=True)
+    table = subprocess.run([tools[2], "--dyn-syms", co], check=True, capture_output=True, text=True).stdout
+    rows = [l.split() for l in table.splitlines() if l.strip().endswith("scratch")]
+    assert rows, "no symbol named *scratch in the device image's dynamic symbols"
+    assert all("GLOBAL" in r and "OBJECT" in r for r in rows), rows
+    assert any(int(r[2]) == hcsa.DLLM_SELECT_STATIC_BYTES for r in rows), rows
+    _ = shutil
+
+
 def test_pack_argument_checks():
     b = good_batch()
     L = hcsa.lib()
