@@ -23,7 +23,7 @@ SOURCES = ["api.hip", "select_kernels.hip", "pack_kernels.hip", "attend_f32.hip"
            "attend_dense_bf16.hip"]
 
 # packed-fp32 VALU forms are switched off for all device code
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-I", INCLUDE, "-I", CSRC]
 

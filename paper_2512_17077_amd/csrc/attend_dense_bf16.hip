@@ -1,93 +1,327 @@
 // Refresh-phase attention (Section 2.3, Eq. 3): dense bidirectional softmax attention, bf16 inputs,
 // fp32 softmax state and accumulators, on the gfx950 matrix cores.  This path is a dense
 // contraction (4*Lq*Lkv*D flop per head against O(L*D) bytes), so it is bound by MFMA throughput.
-// Measured on MI355X, MFMA co-issues with v_exp_f32 and plain vector work almost for free; what costs
-// time is everything that makes waves wait: the start and end of a workgroup, workgroup barriers,
-// staging K/V through registers, and LDS read latency.  Hence:
-//   - a workgroup is four waves (128 query rows of one (sequence, head)) and uses 80 KB of LDS, so two
-//     workgroups share a compute unit and run out of phase: one's prologue, epilogue and barrier waits
-//     are covered by the other's matrix work;
-//   - K/V tiles of 64 keys go from global memory straight into LDS (global_load_lds, 16 bytes per
-//     lane), issued right after the tile barrier and due one tile later: no staging registers, no LDS
-//     writes, and the prologue's loads (Q, two K tiles, one V tile) are all in flight at once.  LDS
-//     tiles are XOR-swizzled by row; since the LDS side of such a load is lane-contiguous, the swizzle
-//     is applied to the global chunk each lane fetches (a permutation inside one 2*D-byte row);
-//   - K lives in a ring of three tiles (its scores are computed one step ahead), V in a ring of two;
-//   - the score MFMA chain starts from the accumulator value -m (the running maximum of the raw
-//     scores) instead of 0, so the scores leave the matrix core with the maximum subtracted; one
-//     multiply by softmax_scale * log2(e) per score, done in the stage that has vector slots to
-//     spare, makes them base-2 logits (Q is NOT pre-scaled: rounding the scaled queries to bf16
-//     again costs 2e-2 of output accuracy at logits around 20);
-//   - the running maximum is raised lazily (only when a score exceeds it by more than 2^8, so
-//     probabilities may exceed 1 until then) behind a uniform branch;
-//   - the key loop is unrolled over one common turn of both rings (twelve 32-key steps), so every LDS
-//     address is a register fixed before the loop plus an immediate offset.
 //
-// Each wave keeps its 32 queries as MFMA B operands in registers for the whole pass and walks the keys
-// in steps of 32 with a software pipeline:
-//   stage 1   S^T(i+1) = K * Q^T - m      (MFMA, A by ds_read_b128)  ||  exp2 of step i, keys 0..15
-//   stage 2   O^T += V^T P^T, keys 0..15  (MFMA, A by ds_read_b64_tr) ||  exp2 of step i, keys 16..31
-//   stage 3   O^T += V^T P^T, keys 16..31 (MFMA)                      ||  scale, row maxima of step i+1
+// Shape of the kernel
+//   - A workgroup is four waves, one per SIMD, and owns 256 query rows of one (sequence, head); a wave
+//     owns 64 of them as two blocks of 32.  Every K operand (ds_read_b128) and every V^T operand
+//     (ds_read_b64_tr_b16) fetched from LDS feeds two MFMAs, one per block, which halves the LDS
+//     operand traffic per flop, and the two blocks give the wave independent work to interleave.
+//   - K/V tiles of 64 keys go from global memory straight into LDS (global_load_lds, 16 bytes per
+//     lane), two tiles ahead of their use, into rings of four tiles each (128 KB at D = 128); one
+//     workgroup barrier per tile.  LDS tiles are XOR-swizzled by row; since the LDS side of such a load
+//     is lane-contiguous, the swizzle is applied to the global chunk each lane fetches.
+//   - Keys are walked in steps of 32 with a three-deep software pipeline.  Iteration j issues
+//         S^T(j+1) = K(j+1) Q^T          16 MFMAs (D = 128), A by ds_read_b128 one iteration ahead
+//         P(j)     = exp2(S(j) z - m z)   vector work on the scores of the previous iteration
+//         O^T     += V(j-1)^T P(j-1)^T    16 MFMAs, A by ds_read_b64_tr_b16 in the same iteration
+//     so the matrix work of an iteration does not depend on its vector work and the issue order can
+//     alternate them freely (one MFMA, then a few vector and LDS instructions, and so on).
+//   - Q is not pre-scaled (rounding the scaled queries to bf16 again costs 2e-2 of output accuracy at
+//     logits around 20): scores leave the matrix core raw, and one fused multiply-add per score,
+//     s * z - m * z with z = softmax_scale * log2(e), makes them base-2 logits relative to the running
+//     maximum m.
+//   - m is raised lazily (only when a score exceeds it by more than 2^8, so probabilities may exceed 1
+//     until then) behind one uniform branch per iteration.  When it is raised after iteration j, the
+//     row sums are rescaled at once; the output accumulators, which still have to take P(j) V(j) at the
+//     old scale during iteration j+1, are rescaled one iteration later.
+//   - The loop is unrolled over one turn of the rings (eight steps), so every LDS address is a register
+//     fixed before the loop plus an immediate offset.
 #include <type_traits>
+#include <utility>
 
 #include "attn_tile.h"
-
+#include "attend_dense_step.inc"
 
 namespace dllm {
 
-#ifndef DLLM_S3V
-#define DLLM_S3V 7
-#endif
 constexpr int kDenseK = 64;          // keys per LDS tile
-constexpr int kDenseRingK = 3;       // K tiles resident in LDS
-constexpr int kDenseRingV = 2;       // V tiles resident in LDS
+constexpr int kDenseRing = 4;        // K tiles, and V tiles, resident in LDS
+constexpr int kDenseWaves = 4;       // waves per workgroup
+constexpr int kDenseQB = 2;          // 32-query blocks per wave
+constexpr int kDenseRows = kDenseWaves * kDenseQB * 32;   // query rows per workgroup
 constexpr float kLazyStep = 8.0f;    // log2 of the growth that forces a rescale
 
-// NQB: 32-query blocks per wave; WAVES: waves per workgroup
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+
+// The state a wave carries through the key loop, bound to the registers the step text of
+// attend_dense_step.inc names.
+//   a[0 : 16*2*NDB)          acc   O^T accumulators [qb][db][16]
+//   a[.. +  4*2*NT)          q     Q^T operands [qb][t][4]
+//   v[96:127], v[128:159]    st_a, st_b   raw scores of two consecutive steps, [qb][16]
+//   v[160:175], v[176:191]   pb_a, pb_b   packed probabilities of two consecutive steps, [qb][u][4]
+//   v[192 : 192 + 4*NT)      kop   K operands of the next score chain, [t][4]
+//   v[80:95]                 addr  LDS byte addresses: K operand [t], then V^T operand [rd][db] from +8
+//   v70 .. v75               lsum[2], nmz[2] (= -m z per block), mx[2] (lane maxima of the newest scores)
+//   v[76:79], v[224:255]     scratch of a step (logits in flight, V^T operand buffers)
+// C++ code may read and write the v-register variables between steps like any others, and may write q;
+// the accumulators are only ever handed from one assembly block to the next (this compiler cannot take
+// single elements out of an a-register tuple that an assembly block has written), so clearing,
+// rescaling and reading them are assembly blocks too.
+template <int D>
+struct DenseState;
+
+// What the first step of a tile needs to request the tile two ahead: the tile's first K and V row
+// (wave-uniform), the byte offset of each of this lane's 16-byte chunks from there, and the LDS address
+// of this wave's slice of a load round.
+template <int NLD>
+struct DenseTileLoad {
+  const char *k, *v;
+  uint32_t off[NLD];
+  uint32_t wave_lds;
+};
+
+#define DLLM_DENSE_SCRATCH                                                                                        \
+  "v76", "v77", "v78", "v79", "v224", "v225", "v226", "v227", "v228", "v229", "v230", "v231", "v232", "v233", "v234", \
+      "v235", "v236", "v237", "v238", "v239", "v240", "v241", "v242", "v243", "v244", "v245", "v246", "v247", "v248", \
+      "v249", "v250", "v251", "v252", "v253", "v254", "v255"
+#define DLLM_R16(k, x) "=v"(x[16 * (k) + 0]), "=v"(x[16 * (k) + 1]), "=v"(x[16 * (k) + 2]), "=v"(x[16 * (k) + 3]), \
+      "=v"(x[16 * (k) + 4]), "=v"(x[16 * (k) + 5]), "=v"(x[16 * (k) + 6]), "=v"(x[16 * (k) + 7]),                  \
+      "=v"(x[16 * (k) + 8]), "=v"(x[16 * (k) + 9]), "=v"(x[16 * (k) + 10]), "=v"(x[16 * (k) + 11]),               \
+      "=v"(x[16 * (k) + 12]), "=v"(x[16 * (k) + 13]), "=v"(x[16 * (k) + 14]), "=v"(x[16 * (k) + 15])
+
+template <>
+struct DenseState<128> {
+  static constexpr int kAcc = 128;   // accumulator registers
+  f32x16 acc[8], q[4], st_a[2], st_b[2], kop[2], pb_a, pb_b;
+  float lsum[2], nmz[2], mx[2];   // v70, v71; v72, v73 (= -m z per block); v74, v75 (lane maxima of the newest scores)
+  i32x16 addr;
+#define DLLM_ACC_OUT                                                                                          \
+  "={a[0:15]}"(acc[0]), "={a[16:31]}"(acc[1]), "={a[32:47]}"(acc[2]), "={a[48:63]}"(acc[3]),                  \
+      "={a[64:79]}"(acc[4]), "={a[80:95]}"(acc[5]), "={a[96:111]}"(acc[6]), "={a[112:127]}"(acc[7])
+#define DLLM_ACC_TIED "0"(acc[0]), "1"(acc[1]), "2"(acc[2]), "3"(acc[3]), "4"(acc[4]), "5"(acc[5]), "6"(acc[6]), "7"(acc[7])
+#define DLLM_ACC_IN                                                                                           \
+  "{a[0:15]}"(acc[0]), "{a[16:31]}"(acc[1]), "{a[32:47]}"(acc[2]), "{a[48:63]}"(acc[3]), "{a[64:79]}"(acc[4]), \
+      "{a[80:95]}"(acc[5]), "{a[96:111]}"(acc[6]), "{a[112:127]}"(acc[7])
+#define DLLM_Q_IN "{a[128:143]}"(q[0]), "{a[144:159]}"(q[1]), "{a[160:175]}"(q[2]), "{a[176:191]}"(q[3])
+  template <bool AB, int KOFF, int VOFF0, int VOFF1, int LK, int LV>
+  __device__ __forceinline__ void step(float zs, const DenseTileLoad<4>& tl, uint64_t& grow) {
+    if constexpr (AB)
+      asm volatile(DLLM_DENSE_STEP_128_AB
+                   : DLLM_ACC_OUT, "={v[128:143]}"(st_b[0]), "={v[144:159]}"(st_b[1]), "={v[160:175]}"(pb_a),
+                     "={v[192:207]}"(kop[0]), "={v[208:223]}"(kop[1]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v75}"(mx[1]), [grow] "=s"(grow)
+                   : DLLM_ACC_TIED, "11"(kop[0]), "12"(kop[1]), "13"(lsum[0]), "14"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[96:111]}"(st_a[0]),
+                     "{v[112:127]}"(st_a[1]), "{v[176:191]}"(pb_b), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep),
+                     [koff] "n"(KOFF), [voff0] "n"(VOFF0), [voff1] "n"(VOFF1), [kt] "s"(tl.k), [vt] "s"(tl.v),
+                     [lo0] "v"(tl.off[0]), [lo1] "v"(tl.off[1]), [lo2] "v"(tl.off[2]), [lo3] "v"(tl.off[3]),
+                     [wl] "s"(tl.wave_lds), [lk] "n"(LK), [lv] "n"(LV)
+                   : "memory", "m0", "scc", DLLM_DENSE_SCRATCH);
+    else
+      asm volatile(DLLM_DENSE_STEP_128_BA
+                   : DLLM_ACC_OUT, "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1]), "={v[176:191]}"(pb_b),
+                     "={v[192:207]}"(kop[0]), "={v[208:223]}"(kop[1]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v75}"(mx[1]), [grow] "=s"(grow)
+                   : DLLM_ACC_TIED, "11"(kop[0]), "12"(kop[1]), "13"(lsum[0]), "14"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[128:143]}"(st_b[0]),
+                     "{v[144:159]}"(st_b[1]), "{v[160:175]}"(pb_a), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep),
+                     [koff] "n"(KOFF), [voff0] "n"(VOFF0), [voff1] "n"(VOFF1)
+                   : "memory", DLLM_DENSE_SCRATCH);
+  }
+  // the closing P V product, with the probabilities of pb_a (A) or pb_b; `ad`: addr with the V row
+  // offset added to the V^T operand addresses (it is not a compile-time constant here)
+  template <bool A>
+  __device__ __forceinline__ void tail(i32x16 ad) {
+    if constexpr (A)
+      asm volatile(DLLM_DENSE_TAIL_128_A
+                   : DLLM_ACC_OUT
+                   : DLLM_ACC_TIED, "{v[160:175]}"(pb_a), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 256)
+                   : "memory", DLLM_DENSE_SCRATCH);
+    else
+      asm volatile(DLLM_DENSE_TAIL_128_B
+                   : DLLM_ACC_OUT
+                   : DLLM_ACC_TIED, "{v[176:191]}"(pb_b), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 256)
+                   : "memory", DLLM_DENSE_SCRATCH);
+  }
+  // S^T(0) into st_a from the K operands in kop
+  __device__ __forceinline__ void score0() {
+    asm volatile(DLLM_DENSE_SCORE0_128
+                 : "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1])
+                 : "{v[192:207]}"(kop[0]), "{v[208:223]}"(kop[1]), DLLM_Q_IN);
+  }
+  __device__ __forceinline__ void acc_clear() { asm volatile(DLLM_DENSE_ACC_INIT_128 : DLLM_ACC_OUT); }
+  // acc[qb] *= al[qb]; waits out the matrix pipe first (results may be read only 12 wait states after the
+  // MFMA was issued, and nothing but software enforces it)
+  __device__ __forceinline__ void acc_scale(float al0, float al1) {
+    asm volatile(DLLM_DENSE_ACC_SCALE_128 : DLLM_ACC_OUT : DLLM_ACC_TIED, [al0] "v"(al0), [al1] "v"(al1) : DLLM_DENSE_SCRATCH);
+  }
+  // all accumulators of block qb, head_dim block db, after the matrix pipe has drained
+  __device__ __forceinline__ void acc_read(float (&x)[kAcc]) {
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    asm volatile(DLLM_DENSE_ACC_READ_0 : DLLM_R16(0, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_1 : DLLM_R16(1, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_2 : DLLM_R16(2, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_3 : DLLM_R16(3, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_4 : DLLM_R16(4, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_5 : DLLM_R16(5, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_6 : DLLM_R16(6, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_7 : DLLM_R16(7, x) : DLLM_ACC_IN);
+  }
+#undef DLLM_ACC_OUT
+#undef DLLM_ACC_TIED
+#undef DLLM_ACC_IN
+#undef DLLM_Q_IN
+  // element access (indices are compile-time constants after unrolling)
+  __device__ __forceinline__ float q_get(int qb, int t, int c) const { return q[2 * qb + t / 4][4 * (t % 4) + c]; }
+  __device__ __forceinline__ void q_set(int qb, int t, int c, float x) { q[2 * qb + t / 4][4 * (t % 4) + c] = x; }
+  __device__ __forceinline__ float kop_get(int t, int c) const { return kop[t / 4][4 * (t % 4) + c]; }
+  __device__ __forceinline__ void kop_set(int t, int c, float x) { kop[t / 4][4 * (t % 4) + c] = x; }
+};
+
+template <>
+struct DenseState<64> {
+  static constexpr int kAcc = 64;
+  f32x16 acc[4], q[2], st_a[2], st_b[2], kop[1], pb_a, pb_b;
+  float lsum[2], nmz[2], mx[2];   // v70, v71; v72, v73 (= -m z per block); v74, v75 (lane maxima of the newest scores)
+  i32x16 addr;
+#define DLLM_ACC_OUT "={a[0:15]}"(acc[0]), "={a[16:31]}"(acc[1]), "={a[32:47]}"(acc[2]), "={a[48:63]}"(acc[3])
+#define DLLM_ACC_TIED "0"(acc[0]), "1"(acc[1]), "2"(acc[2]), "3"(acc[3])
+#define DLLM_ACC_IN "{a[0:15]}"(acc[0]), "{a[16:31]}"(acc[1]), "{a[32:47]}"(acc[2]), "{a[48:63]}"(acc[3])
+#define DLLM_Q_IN "{a[64:79]}"(q[0]), "{a[80:95]}"(q[1])
+  template <bool AB, int KOFF, int VOFF0, int VOFF1, int LK, int LV>
+  __device__ __forceinline__ void step(float zs, const DenseTileLoad<2>& tl, uint64_t& grow) {
+    if constexpr (AB)
+      asm volatile(DLLM_DENSE_STEP_64_AB
+                   : DLLM_ACC_OUT, "={v[128:143]}"(st_b[0]), "={v[144:159]}"(st_b[1]), "={v[160:175]}"(pb_a),
+                     "={v[192:207]}"(kop[0]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v75}"(mx[1]), [grow] "=s"(grow)
+                   : DLLM_ACC_TIED, "7"(kop[0]), "8"(lsum[0]), "9"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[96:111]}"(st_a[0]), "{v[112:127]}"(st_a[1]),
+                     "{v[176:191]}"(pb_b), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep), [koff] "n"(KOFF), [voff0] "n"(VOFF0),
+                     [voff1] "n"(VOFF1), [kt] "s"(tl.k), [vt] "s"(tl.v), [lo0] "v"(tl.off[0]), [lo1] "v"(tl.off[1]),
+                     [wl] "s"(tl.wave_lds), [lk] "n"(LK), [lv] "n"(LV)
+                   : "memory", "m0", "scc", DLLM_DENSE_SCRATCH);
+    else
+      asm volatile(DLLM_DENSE_STEP_64_BA
+                   : DLLM_ACC_OUT, "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1]), "={v[176:191]}"(pb_b),
+                     "={v[192:207]}"(kop[0]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v75}"(mx[1]), [grow] "=s"(grow)
+                   : DLLM_ACC_TIED, "7"(kop[0]), "8"(lsum[0]), "9"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[128:143]}"(st_b[0]), "{v[144:159]}"(st_b[1]),
+                     "{v[160:175]}"(pb_a), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep), [koff] "n"(KOFF), [voff0] "n"(VOFF0),
+                     [voff1] "n"(VOFF1)
+                   : "memory", DLLM_DENSE_SCRATCH);
+  }
+  template <bool A>
+  __device__ __forceinline__ void tail(i32x16 ad) {
+    if constexpr (A)
+      asm volatile(DLLM_DENSE_TAIL_64_A
+                   : DLLM_ACC_OUT
+                   : DLLM_ACC_TIED, "{v[160:175]}"(pb_a), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 128)
+                   : "memory", DLLM_DENSE_SCRATCH);
+    else
+      asm volatile(DLLM_DENSE_TAIL_64_B
+                   : DLLM_ACC_OUT
+                   : DLLM_ACC_TIED, "{v[176:191]}"(pb_b), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 128)
+                   : "memory", DLLM_DENSE_SCRATCH);
+  }
+  __device__ __forceinline__ void score0() {
+    asm volatile(DLLM_DENSE_SCORE0_64
+                 : "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1])
+                 : "{v[192:207]}"(kop[0]), DLLM_Q_IN);
+  }
+  __device__ __forceinline__ void acc_clear() { asm volatile(DLLM_DENSE_ACC_INIT_64 : DLLM_ACC_OUT); }
+  __device__ __forceinline__ void acc_scale(float al0, float al1) {
+    asm volatile(DLLM_DENSE_ACC_SCALE_64 : DLLM_ACC_OUT : DLLM_ACC_TIED, [al0] "v"(al0), [al1] "v"(al1) : DLLM_DENSE_SCRATCH);
+  }
+  __device__ __forceinline__ void acc_read(float (&x)[kAcc]) {
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    asm volatile(DLLM_DENSE_ACC_READ_0 : DLLM_R16(0, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_1 : DLLM_R16(1, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_2 : DLLM_R16(2, x) : DLLM_ACC_IN);
+    asm volatile(DLLM_DENSE_ACC_READ_3 : DLLM_R16(3, x) : DLLM_ACC_IN);
+  }
+#undef DLLM_ACC_OUT
+#undef DLLM_ACC_TIED
+#undef DLLM_ACC_IN
+#undef DLLM_Q_IN
+  __device__ __forceinline__ float q_get(int qb, int t, int c) const { return q[qb][4 * t + c]; }
+  __device__ __forceinline__ void q_set(int qb, int t, int c, float x) { q[qb][4 * t + c] = x; }
+  __device__ __forceinline__ float kop_get(int t, int c) const { return kop[0][4 * t + c]; }
+  __device__ __forceinline__ void kop_set(int t, int c, float x) { kop[0][4 * t + c] = x; }
+};
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ... in order
+template <typename F, int... C>
+__device__ __forceinline__ void for_each_round(F& f, std::integer_sequence<int, C...>) {
+  (f(std::integral_constant<int, C>{}), ...);
+}
+
 // which: 1 = only sequences flagged dense in seq_mode; 2 = every sequence
-template <int D, int NQB, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_bf16_kernel(
+template <int D>
+__global__ __launch_bounds__(kDenseWaves * 64, 1) void attend_dense_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const uint8_t* __restrict__ seq_mode,
     int which, uint16_t* __restrict__ o, Shape s) {
+  constexpr int NQB = kDenseQB;
   constexpr int CH = D / 8;
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = kDenseK * ROWB;
-  constexpr int VBASE = kDenseRingK * TILEB;     // V tiles follow the K tiles
-  constexpr int NTHREADS = WAVES * 64;
-  constexpr int QROWS = WAVES * 32 * NQB;
+  constexpr int VBASE = kDenseRing * TILEB;      // V ring follows the K ring
+  constexpr int NTHREADS = kDenseWaves * 64;
   constexpr int NLD = kDenseK * CH / NTHREADS;   // 16-byte loads per lane, tile and tensor
   constexpr int NT = D / 16;
   constexpr int NDB = D / 32;
-  constexpr int ROUND = 2 * kDenseRingK * kDenseRingV;   // steps in one common turn of both rings
+  constexpr int ROUND = 2 * kDenseRing;          // steps in one turn of the rings
   static_assert(NLD >= 1 && kDenseK * CH % NTHREADS == 0, "tile does not split evenly over the threads");
+  static_assert(kDenseRing * TILEB <= 65536, "ring offsets must fit the 16-bit LDS offset field");
 
-  __shared__ __attribute__((aligned(16))) char smem[(kDenseRingK + kDenseRingV) * TILEB];   // K ring, V ring
+  __shared__ __attribute__((aligned(16))) char smem[2 * kDenseRing * TILEB];   // K ring, V ring
 
   // Workgroups are handed to the eight XCDs round-robin by launch order, and each XCD has its own
-  // L2.  Renumber so that the query tiles of one (sequence, head), which all stream the same K/V,
-  // land on one XCD (launch ids equal modulo 8) and share its L2 instead of fetching K/V eight
-  // times, while consecutive (sequence, head) pairs still go to different XCDs.
-  const int nx = gridDim.x, groups = gridDim.y * gridDim.z;
+  // L2.  Renumber so that the workgroups that stream the same K/V -- the query tiles of the query
+  // heads that share one KV head of one sequence -- land on one XCD (launch ids equal modulo 8)
+  // and share its L2, while consecutive (sequence, KV head) pairs go to different XCDs.
+  const int nx = gridDim.x, units = s.hkv * gridDim.z;
   const int n = blockIdx.x + nx * (blockIdx.y + gridDim.y * blockIdx.z);
-  int qtile = blockIdx.x, gi = blockIdx.y + gridDim.y * blockIdx.z;
-  if ((groups & 7) == 0) {
+  int qtile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if ((units & 7) == 0) {
+    const int per_unit = s.group * nx;
     const int j = n >> 3;   // position in this XCD's own launch sequence
-    qtile = j % nx;
-    gi = (j / nx) * 8 + (n & 7);
+    const int r = j % per_unit, unit = (j / per_unit) * 8 + (n & 7);
+    qtile = r % nx;
+    h = (unit % s.hkv) * s.group + r / nx;
+    b = unit / s.hkv;
   }
-  const int h = gi % gridDim.y, b = gi / gridDim.y;
   if (which == 1 && !(seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE)) return;
   const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
-  const int qbase = qtile * QROWS;
+  const int qbase = qtile * kDenseRows;
   if (qbase >= nq) return;
   const int kv0 = cu_kv[b], L = cu_kv[b + 1] - kv0;
   const int g = h / s.group;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int col = lane & 31, hf = lane >> 5;
+#ifdef DLLM_DENSE_STAMPS
+  // timing experiments only: every workgroup leaves shader-clock counts in its own first output row
+  // (and stores no outputs): [0] entry, [1] loop start, [2] loop end, [3] end, [4..11] cycles spent in
+  // steps at ring position R, [12] slowest step, [13] number of steps over 3000 cycles
+  const uint64_t rt_entry = __builtin_amdgcn_s_memrealtime();   // 100 MHz
+  uint64_t t_entry = __builtin_readcyclecounter(), t_loop0 = 0, t_prev = 0, by_r[8] = {0, 0, 0, 0, 0, 0, 0, 0},
+           t_max = 0, n_slow = 0, t_part = 0, parts[4] = {0, 0, 0, 0};
+#define DLLM_STAMP_PART(i)                                   \
+  {                                                          \
+    const uint64_t t_now = __builtin_readcyclecounter();     \
+    if (i > 0) parts[i] += t_now - t_part;                   \
+    t_part = t_now;                                          \
+  }
+#define DLLM_STAMP_LOOP_START() t_loop0 = t_prev = __builtin_readcyclecounter()
+#if DLLM_DENSE_STAMPS < 2
+#define DLLM_STAMP_STEP(R)
+#else
+#define DLLM_STAMP_STEP(R)                                  \
+  {                                                         \
+    const uint64_t t_now = __builtin_readcyclecounter();    \
+    const uint64_t dt = t_now - t_prev;                     \
+    by_r[R] += dt;                                          \
+    t_max = dt > t_max ? dt : t_max;                        \
+    n_slow += dt > 3000 ? 1 : 0;                            \
+    t_prev = t_now;                                         \
+  }
+#endif
+#else
+#define DLLM_STAMP_LOOP_START()
+#define DLLM_STAMP_STEP(R)
+#endif
 
   if (L == 0) {   // nothing to attend to: zeros
-    for (int e = tid; e < QROWS * D; e += NTHREADS) {
+    for (int e = tid; e < kDenseRows * D; e += NTHREADS) {
       const int r = qbase + e / D;
       if (r < nq) o[(int64_t(q0 + r) * s.hq + h) * D + e % D] = 0;
     }
@@ -98,63 +332,91 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   const char* vbase = reinterpret_cast<const char*>(v + int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head);
   const int64_t pitch = s.kv_tok * 2;
 
+  DenseState<D> w;
   // LDS addresses, fixed for the whole pass; ring slot, 32-key half and 16-key quarter are immediates
-  int ka[NT], va[2][NDB];
   {
     KAddr<D> kaddr;
     kaddr.init(lane);
     VtAddr<D> vaddr;
     vaddr.init(lane);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) ka[t] = kaddr.off(t);
+    for (int i = 0; i < 16; ++i) w.addr[i] = 0;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) w.addr[t] = kaddr.off(t);
 #pragma unroll
     for (int rd = 0; rd < 2; ++rd)
 #pragma unroll
-      for (int db = 0; db < NDB; ++db) va[rd][db] = VBASE + vaddr.off(rd, db);
+      for (int db = 0; db < NDB; ++db) w.addr[8 + NDB * rd + db] = VBASE + vaddr.off(rd, db);
   }
   // Global side of the tile loads: this lane's chunk f = i * NTHREADS + tid of a tile lands at LDS
   // byte 16 * f, i.e. row f / CH, chunk slot f % CH, and must hold chunk (slot ^ swizzle(row)) of
   // that row.  Rows past the end of the sequence re-read its last row (their keys are masked).
-  int ld_row[NLD], ld_col[NLD];
   uint32_t ld_off[NLD];   // byte offset of the chunk from the tile's first row (fits: checked on the host)
 #pragma unroll
   for (int i = 0; i < NLD; ++i) {
     const int f = i * NTHREADS + tid, row = f / CH;
-    ld_row[i] = row;
-    ld_col[i] = ((f % CH) ^ tile_swz<D>(row)) << 4;
-    ld_off[i] = uint32_t(row) * uint32_t(pitch) + uint32_t(ld_col[i]);
+    ld_off[i] = uint32_t(row) * uint32_t(pitch) + uint32_t(((f % CH) ^ tile_swz<D>(row)) << 4);
+  }
+  // the same for the last tile when the sequence ends inside it: rows past the end re-read the last row
+  const int ntiles = (L + kDenseK - 1) / kDenseK;
+  uint32_t ld_off_last[NLD];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int f = i * NTHREADS + tid, row = min(f / CH, L - 1 - (ntiles - 1) * kDenseK);
+    ld_off_last[i] = uint32_t(row) * uint32_t(pitch) + uint32_t(((f % CH) ^ tile_swz<D>(f / CH)) << 4);
   }
   // this wave's slice of each load round, as an LDS byte address
   const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_addr(smem) + wave * 64 * 16);
-  auto load_tile = [&](const char* base, int tile, int lds_off) {
+  auto load_tile = [&](const char* base, int tile, auto lds_off) __attribute__((always_inline)) {
+    constexpr int kLdsOff = decltype(lds_off)::value;
     const int t0 = tile * kDenseK;
     if (t0 + kDenseK <= L) {   // whole tile inside the sequence: uniform tile address + fixed lane offsets
       const char* tbase = base + int64_t(t0) * pitch;
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) load16_to_lds(tbase, ld_off[i], wave_lds + lds_off + i * NTHREADS * 16);
+      auto round = [&](auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        load16_to_lds<kLdsOff + i * NTHREADS * 16>(tbase, ld_off[i], wave_lds);
+      };
+      for_each_round(round, std::make_integer_sequence<int, NLD>{});
     } else {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int row = min(t0 + ld_row[i], L - 1);
-        load16_to_lds(base + row * pitch + ld_col[i], wave_lds + lds_off + i * NTHREADS * 16);
-      }
+      auto round = [&](auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        const int f = i * NTHREADS + tid, r = f / CH;
+        const int row = min(t0 + r, L - 1);
+        load16_to_lds<kLdsOff + i * NTHREADS * 16>(base + row * pitch + (((f % CH) ^ tile_swz<D>(r)) << 4),
+                                                   wave_lds);
+      };
+      for_each_round(round, std::make_integer_sequence<int, NLD>{});
     }
   };
+#define DLLM_IC(x) std::integral_constant<int, (x)> {}
 
   // the first tiles are requested before anything else, so their latency overlaps the Q loads
   const int rem = L % 32;
   const int nsteps = L / 32 + (rem ? 1 : 0);
-  const int ntiles = (L + kDenseK - 1) / kDenseK;
-  load_tile(kbase, 0, 0);
-  load_tile(vbase, 0, VBASE);
-  if (ntiles > 1) load_tile(kbase, 1, TILEB);
+  load_tile(kbase, 0, DLLM_IC(0));
+  load_tile(vbase, 0, DLLM_IC(VBASE));
+  if (ntiles > 1) {
+    load_tile(kbase, 1, DLLM_IC(TILEB));
+    load_tile(vbase, 1, DLLM_IC(VBASE + TILEB));
+  }
+#ifdef DLLM_DENSE_FILL_RING   // timing experiments only: all four ring slots filled once (tiles 0..3)
+  if (ntiles > 3) {
+    load_tile(kbase, 2, DLLM_IC(2 * TILEB));
+    load_tile(vbase, 2, DLLM_IC(VBASE + 2 * TILEB));
+    load_tile(kbase, 3, DLLM_IC(3 * TILEB));
+    load_tile(vbase, 3, DLLM_IC(VBASE + 3 * TILEB));
+  }
+#endif
+  // Iteration 0 multiplies an all-zero P with the second half of ring slot 3 of V (the step "before
+  // the first"): clear it, so that no stale NaN pattern meets the zeros.  Tile 3 lands there later.
+  {
+    constexpr int kHalf = 32 * ROWB;
+    for (int e = tid * 16; e < kHalf; e += NTHREADS * 16)
+      *reinterpret_cast<v4u*>(smem + VBASE + 3 * TILEB + kHalf + e) = v4u{0u, 0u, 0u, 0u};
+  }
 
-  // Q^T operands: lane (col = query, hf) holds Q[query][16t + 8hf .. +8) for every step t, as given:
-  // scaling them here would round them to bf16 a second time, an error in the logit that grows with
-  // the logit (2e-2 in the output at logits around 20); the scale is applied to the fp32 scores
+  // Q^T operands: lane (col = query, hf) holds Q[query][16t + 8hf .. +8) for every step t, as given
   const float zscale = s.scale * kLog2e;   // > 0; scores * zscale are base-2 logits
-  const float inv_zscale = 1.0f / zscale;
-  v4u qreg[NQB][NT];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int qi = qbase + (wave * NQB + qb) * 32 + col;
@@ -163,49 +425,37 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
     for (int t = 0; t < NT; ++t) {
       v4u x = v4u{0u, 0u, 0u, 0u};
       if (qi < nq) x = *reinterpret_cast<const v4u*>(qp + 16 * t + 8 * hf);
-      qreg[qb][t] = x;
+      w.q_set(qb, t, 0, __uint_as_float(x.x));
+      w.q_set(qb, t, 1, __uint_as_float(x.y));
+      w.q_set(qb, t, 2, __uint_as_float(x.z));
+      w.q_set(qb, t, 3, __uint_as_float(x.w));
     }
   }
-
-  // running maximum m (of the raw scores q.k), kept negated in all 16 registers of an accumulator so
-  // that it can seed the score MFMA chain; row sum; output accumulators
-  f32x16 negm[NQB];
-  float lsum[NQB];
-  f32x16 acc[NQB][NDB];
+  // per query (lane pair l, l ^ 32): the row sum, -m * z for the running maximum m of the raw scores
+  // (w.lsum, w.nmz), the factor the output accumulators still have to take, and the accumulators
+  float palpha[NQB];
+  bool pending = false;   // some palpha != 1 (uniform)
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    lsum[qb] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) negm[qb][i] = 0.0f;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[qb][db][i] = 0.0f;
+    palpha[qb] = 1.0f;
+    w.lsum[qb] = 0.0f;
   }
+  w.acc_clear();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) w.pb_a[i] = w.pb_b[i] = 0.0f;
 
   // A operands of one step's score chain: rows = 32 keys at byte offset `koff` of the K ring
-  auto k_operands = [&](v4u (&kop)[NT], int koff) {
+  auto k_operands = [&](int koff) __attribute__((always_inline)) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) kop[t] = *reinterpret_cast<const v4u*>(smem + ka[t] + koff);
+    for (int t = 0; t < NT; ++t) {
+      const v4u x = *reinterpret_cast<const v4u*>(smem + w.addr[t] + koff);
+      w.kop_set(t, 0, __uint_as_float(x.x));
+      w.kop_set(t, 1, __uint_as_float(x.y));
+      w.kop_set(t, 2, __uint_as_float(x.z));
+      w.kop_set(t, 3, __uint_as_float(x.w));
+    }
   };
-  // scores of a 32-key step relative to the running maxima: rows = keys, columns = this wave's queries
-  auto score_chain = [&](f32x16 (&st)[NQB], const v4u (&kop)[NT]) {
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) st[qb] = negm[qb];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) st[qb] = mfma_bf16(kop[t], qreg[qb][t], st[qb]);
-  };
-  // raw scores minus the running maximum -> base-2 logits
-  auto to_logits = [&](f32x16 (&st)[NQB]) {
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) st[qb][i] *= zscale;
-  };
-  auto mask_tail = [&](f32x16 (&st)[NQB], int nvalid) {   // keys past the end get no weight
-    asm volatile("" ::: "memory");   // keep the caller's test a real (uniform) branch
+  auto mask_tail = [&](f32x16 (&st)[NQB], int nvalid) __attribute__((always_inline)) {   // keys past the end get no weight
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
@@ -215,201 +465,155 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
       }
   };
   // largest score of a step per lane (a query's scores sit in the lane pair l, l ^ 32)
-  auto lane_max = [&](const f32x16& st) -> float {
+  auto lane_max = [&](const f32x16& st) __attribute__((always_inline)) -> float {
     float mx = fmaxf(st[0], st[1]);
 #pragma unroll
     for (int i = 2; i < 16; i += 2) mx = fmaxf(fmaxf(mx, st[i]), st[i + 1]);
     return mx;
   };
-  // Raise the running maxima by delta >= 0 (in base-2 logits) per query and rescale what was
-  // accumulated under the old ones, including the logits `st` already computed relative to them.
-  auto raise = [&](f32x16 (&st)[NQB], const float (&delta)[NQB]) {
+  // What the first step of each tile needs to request the tile two ahead (see the step text).  Past
+  // the last tile the last one is requested again, into a ring slot nobody reads any more.
+  const int64_t tile_bytes = int64_t(kDenseK) * pitch;
+  const bool last_whole = ntiles * kDenseK == L;
+  const int load_idx = min(2, ntiles - 1);   // tile the first tile boundary requests
+  DenseTileLoad<NLD> tl;
+  tl.k = kbase + load_idx * tile_bytes;
+  tl.v = vbase + load_idx * tile_bytes;
+  tl.wave_lds = wave_lds;
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const float alpha = __builtin_amdgcn_exp2f(-delta[qb]);
-      const float delta_raw = delta[qb] * inv_zscale;
-      lsum[qb] *= alpha;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        negm[qb][i] -= delta_raw;
-        st[qb][i] -= delta[qb];
-      }
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[qb][db][e] *= alpha;
-    }
-  };
-  // probabilities of keys 16u .. 16u+15 of a step, packed as the B operand of the P*V MFMAs
-  auto probs = [&](const f32x16 (&st)[NQB], int u, v4u (&pb)[NQB]) {
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      uint32_t w[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float p0 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j]);
-        const float p1 = __builtin_amdgcn_exp2f(st[qb][8 * u + 2 * j + 1]);
-        w[j] = cvt_pk_bf16(p0, p1);
-        lsum[qb] = add_pair_bf16(w[j], lsum[qb]);
-      }
-      pb[qb] = v4u{w[0], w[1], w[2], w[3]};
-    }
-  };
-  // A operands of one 16-key slice of O^T += V^T P^T: V^T blocks of 32 head_dim rows x 16 keys
-  auto v_operands = [&](v4u (&vop)[NDB], int voff) {
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      const v2u lo = lds_read_tr16(smem + va[0][db] + voff);
-      const v2u hi = lds_read_tr16(smem + va[1][db] + voff);
-      vop[db] = v4u{lo.x, lo.y, hi.x, hi.y};
-    }
-  };
-  auto accumulate = [&](const v4u (&vop)[NDB], const v4u (&pb)[NQB]) {
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) acc[qb][db] = mfma_bf16(vop[db], pb[qb], acc[qb][db]);
-  };
+  for (int i = 0; i < NLD; ++i) tl.off[i] = (load_idx == ntiles - 1 && !last_whole) ? ld_off_last[i] : ld_off[i];
 
   wait_tile_loads();
   __syncthreads();
 
-  // Issue-order hints: inside a stage, spread the vector and LDS work between the MFMAs so that the
-  // matrix pipe always has the next MFMA waiting behind work that does not depend on it.
-#define DLLM_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-  constexpr int kMfma = 0x008, kValu = 0x002, kTrans = 0x400, kDsRead = 0x100;
-
-  f32x16 st_a[NQB], st_b[NQB];
-  v4u kop[NT];   // K operands of the next score chain, fetched a stage ahead of their use
-  k_operands(kop, 0);
-  score_chain(st_a, kop);
-  to_logits(st_a);
-  if (nsteps == 1 && rem) mask_tail(st_a, rem);
-  // the first step sets the maxima outright (they may be negative); nothing is accumulated yet
+  // scores of step 0, its maxima outright (they may be negative)
+  k_operands(0);
+  w.score0();
+  if (nsteps == 1 && rem) mask_tail(w.st_a, rem);
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const float first = max_across_halves(lane_max(st_a[qb]));
-    const float first_raw = first * inv_zscale;
+  for (int qb = 0; qb < NQB; ++qb) w.nmz[qb] = -(max_across_halves(lane_max(w.st_a[qb])) * zscale);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      negm[qb][i] = -first_raw;
-      st_a[qb][i] -= first;
-    }
-  }
-  k_operands(kop, 32 * ROWB);   // step 1 (stale LDS if there is none; then unused)
+  for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w.st_b[qb][i] = 0.0f;
+  k_operands(32 * ROWB);   // step 1 (stale LDS if there is none; then unused)
 
-  // One 32-key step.  R is its position in the common turn of the rings, which fixes every LDS
-  // offset.  The step multiplies P of step i with V tile (R/2) % 2, half R%2, computes the scores of
-  // step i+1 from K operands fetched during step i-1, and fetches those of step i+2.
-  int i = 0;
-  auto step = [&](auto rc, f32x16 (&cur)[NQB], f32x16 (&nxt)[NQB]) {
+  // Iteration j at position R = j % ROUND of the ring turn, which fixes every LDS offset.  Between two
+  // steps the common path is a handful of scalar instructions and one branch; everything else (the end
+  // of the sequence, the ragged last step, a running maximum to raise, accumulators that still owe a
+  // factor) sits behind that branch.
+  // Between two steps the common path is one test and, after the first step of a tile, the advance of
+  // the tile pointers; everything else (the end of the sequence, the ragged last step, a running
+  // maximum to raise, accumulators that still owe a factor) sits behind that test.  `special` is
+  // set while something other than a grown score asks for the careful path: accumulators that owe a
+  // factor, or the last steps of the sequence (from one ring turn before the end).
+  int j = 0;        // steps done
+  int jb = 0;       // steps done at the start of the current ring turn
+  uint32_t special = 0;   // (kept wave-uniform in a scalar register)
+  int64_t advance = load_idx < ntiles - 1 ? tile_bytes : 0;   // what the tile pointers move by after a tile's first step; 0 once they reached the last tile
+  DLLM_STAMP_LOOP_START();
+  // one step at ring position R (the text, with every offset it needs)
+#define DLLM_RUN_STEP(R, grow)                                                                                  \
+  w.template step<(R) % 2 == 0, ((((R) + 2) % ROUND) / 2) * TILEB + (((R) + 2) % 2) * 32 * ROWB,                 \
+                  ((((R) + ROUND - 1) % ROUND) / 2) * TILEB + (((R) + ROUND - 1) % 2) * 32 * ROWB,               \
+                  ((((R) + ROUND - 1) % ROUND) / 2) * TILEB + (((R) + ROUND - 1) % 2) * 32 * ROWB + 16 * ROWB,   \
+                  (((R) / 2 + 2) % kDenseRing) * TILEB, VBASE + (((R) / 2 + 2) % kDenseRing) * TILEB>(zscale, tl, grow)
+  // what may need doing after step number j - 1 (at ring position R); true when the sequence is finished
+  auto careful = [&](auto rc, uint64_t grow) __attribute__((always_inline)) -> bool {
     constexpr int R = decltype(rc)::value;
-    constexpr int T = R / 2, kb = R % 2;   // tile index modulo the turn
-    constexpr int RN2 = (R + 2) % ROUND;
-    const int tile = i >> 1;
-    if (kb == 0) {
-      // Tile boundary: everyone is done with tile-1, and the loads issued a tile ago (K of tile+1,
-      // V of this tile) have landed.  The slots of tile-1 take K of tile+2 and V of tile+1.
-      wait_tile_loads();
-      __syncthreads();
-      if (tile + 2 < ntiles) load_tile(kbase, tile + 2, ((T + 2) % kDenseRingK) * TILEB);
-      if (tile + 1 < ntiles) load_tile(vbase, tile + 1, VBASE + ((T + 1) % kDenseRingV) * TILEB);
+    if (pending) {   // hand the accumulators the factor they still owe
+      w.acc_scale(palpha[0], palpha[1]);
+      palpha[0] = palpha[1] = 1.0f;
+      pending = false;
     }
-    constexpr int voff = (T % kDenseRingV) * TILEB + kb * 32 * ROWB;
-    v4u pb0[NQB], pb1[NQB], vop0[NDB], vop1[NDB];
-    __builtin_amdgcn_sched_barrier(0);
-    // stage 1: S^T(i+1) chain || exp2 of keys 0..15 of step i || fetch V^T operands of keys 0..15
-    v_operands(vop0, voff);
-    score_chain(nxt, kop);
-    probs(cur, 0, pb0);
+    if (j >= nsteps) return true;
+    // tile requests near the end: the pointers stop at the last tile, whose rows may end early
+    const int next_load = min((j + 1) / 2 + 2, ntiles - 1);   // tile the next boundary requests
+    advance = next_load < ntiles - 1 ? tile_bytes : 0;
+    tl.k = kbase + next_load * tile_bytes;
+    tl.v = vbase + next_load * tile_bytes;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {   // one group per pair of probabilities packed together
-      DLLM_SGB(kMfma, NT * NQB / 4);
-      DLLM_SGB(kDsRead, 2 * NDB / 4);
-      DLLM_SGB(kTrans, 2 * NQB);
-      DLLM_SGB(kValu, 2 * NQB);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // stage 2: O^T += V^T P^T, keys 0..15 || exp2 of keys 16..31 || fetch V^T operands of keys 16..31
-    // the two stages that feed the output accumulators run at raised wave priority: of the two waves
-    // of a SIMD the one in its P*V half gets the issue slots (measured: 1 % on the Refresh workload)
-    __builtin_amdgcn_s_setprio(3);
-    v_operands(vop1, voff + 16 * ROWB);
-    accumulate(vop0, pb0);
-    probs(cur, 1, pb1);
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      DLLM_SGB(kMfma, NQB);
-      DLLM_SGB(kDsRead, 2);
-      DLLM_SGB(kTrans, 8 * NQB / NDB);
-      DLLM_SGB(kValu, 8 * NQB / NDB);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // stage 3: O^T += V^T P^T, keys 16..31 || row maxima of step i+1 || fetch K operands of step i+2
-    k_operands(kop, ((RN2 / 2) % kDenseRingK) * TILEB + (RN2 % 2) * 32 * ROWB);
-    accumulate(vop1, pb1);
-    to_logits(nxt);
-    bool grow = false;
-    float mx[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      mx[qb] = lane_max(nxt[qb]);
-      grow = grow || (mx[qb] > kLazyStep);
-    }
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      DLLM_SGB(kMfma, NQB);
-      DLLM_SGB(kDsRead, NT / NDB);
-      DLLM_SGB(kValu, DLLM_S3V * NQB);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_setprio(0);
-    ++i;
-    // Rare path, one uniform branch: the next step is the ragged last one (mask the keys past the end,
-    // which were scored from a repeated row), or some score outgrew its running maximum.
-    const bool ragged = rem != 0 && i + 1 == nsteps;
-    if (__builtin_expect((__builtin_amdgcn_ballot_w64(grow) != 0 || ragged) && i < nsteps, 0)) {
+    for (int i = 0; i < NLD; ++i) tl.off[i] = (next_load == ntiles - 1 && !last_whole) ? ld_off_last[i] : ld_off[i];
+    const bool ragged = rem != 0 && j + 1 == nsteps;
+    if (ragged || grow != 0) {
+      // Mask the ragged last step and raise the running maxima for the scores of step j.  Keys past the
+      // end were scored from copies of the last row (the tile loads clamp the row), so they carry that
+      // row's score and the lane maxima need no second look after masking.
       if (ragged) {
-        mask_tail(nxt, rem);
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) mx[qb] = lane_max(nxt[qb]);
+        if constexpr (R % 2 == 0) mask_tail(w.st_b, rem);
+        else mask_tail(w.st_a, rem);
       }
-      float delta[NQB];
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) delta[qb] = fmaxf(max_across_halves(mx[qb]), 0.0f);
-      raise(nxt, delta);
+      for (int qb = 0; qb < NQB; ++qb) {
+        const float mz_old = -w.nmz[qb];
+        const float mz_new = fmaxf(mz_old, max_across_halves(w.mx[qb]) * zscale);
+        const float alpha = __builtin_amdgcn_exp2f(mz_old - mz_new);
+        w.lsum[qb] *= alpha;
+        palpha[qb] = alpha;
+        w.nmz[qb] = -mz_new;
+      }
+      pending = true;
     }
+    special = __builtin_amdgcn_readfirstlane((pending || j + 2 * ROUND > nsteps) ? 1u : 0u);
+    return false;
   };
-  for (;;) {
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 0>{}, st_a, st_b);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 1>{}, st_b, st_a);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 2>{}, st_a, st_b);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 3>{}, st_b, st_a);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 4>{}, st_a, st_b);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 5>{}, st_b, st_a);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 6>{}, st_a, st_b);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 7>{}, st_b, st_a);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 8>{}, st_a, st_b);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 9>{}, st_b, st_a);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 10>{}, st_a, st_b);
-    if (i >= nsteps) break;
-    step(std::integral_constant<int, 11>{}, st_b, st_a);
+#define DLLM_STEP(R)                                         \
+  {                                                          \
+    uint64_t grow;                                           \
+    DLLM_RUN_STEP(R, grow);                                  \
+    DLLM_STAMP_STEP(R);                                      \
+    if ((R) % 2 == 0) {                                      \
+      tl.k += advance;                                       \
+      tl.v += advance;                                       \
+    }                                                        \
+    if (__builtin_expect((uint32_t(grow) | uint32_t(grow >> 32) | special) != 0, 0)) { \
+      j = jb + (R) + 1;                                      \
+      if (careful(DLLM_IC(R), grow)) break;                  \
+    }                                                        \
   }
+  for (;;) {
+    special = __builtin_amdgcn_readfirstlane((pending || jb + 2 * ROUND > nsteps) ? 1u : 0u);
+    DLLM_STEP(0)
+    DLLM_STEP(1)
+    DLLM_STEP(2)
+    DLLM_STEP(3)
+    DLLM_STEP(4)
+    DLLM_STEP(5)
+    DLLM_STEP(6)
+    DLLM_STEP(7)
+    jb += ROUND;
+  }
+  // the last step's P V product: its probabilities are in pb_a after an odd number of steps, else in pb_b
+  {
+    const int last = nsteps - 1;
+    const int voff = ((last >> 1) % kDenseRing) * TILEB + (last & 1) * 32 * ROWB;
+    i32x16 ad = w.addr;
+#pragma unroll
+    for (int i = 8; i < 16; ++i) ad[i] += voff;
+    if (nsteps & 1) w.template tail<true>(ad);
+    else w.template tail<false>(ad);
+  }
+#ifdef DLLM_DENSE_STAMPS
+  const uint64_t t_loop1 = __builtin_readcyclecounter();
+#endif
+  float accv[DenseState<D>::kAcc];   // [qb][db][16]
+  w.acc_read(accv);
+#ifdef DLLM_DENSE_STAMPS
+  if (tid == 0) {
+    uint64_t* dst = reinterpret_cast<uint64_t*>(o + (int64_t(q0 + qbase) * s.hq + h) * D);
+    dst[0] = t_entry; dst[1] = t_loop0; dst[2] = t_loop1; dst[3] = __builtin_readcyclecounter();
+    for (int r = 0; r < 8; ++r) dst[4 + r] = by_r[r];
+    dst[12] = t_max; dst[13] = n_slow;
+    dst[14] = parts[1]; dst[15] = parts[2]; dst[16] = parts[3];   // load wait, barrier, load issue: sums over the tiles
+    dst[17] = rt_entry; dst[18] = __builtin_amdgcn_s_memrealtime();
+    dst[19] = (uint64_t(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11))) << 32) | __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
+  }
+  return;   // the counts sit where outputs would go
+#endif
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int qi = qbase + (wave * NQB + qb) * 32 + col;
-    const float l = sum_across_halves(lsum[qb]);
+    const float l = sum_across_halves(w.lsum[qb]);
     if (qi < nq) {
       const float inv = 1.0f / l;
 #pragma unroll
@@ -418,8 +622,9 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
           v2u w2;
-          w2.x = cvt_pk_bf16(acc[qb][db][4 * i4 + 0] * inv, acc[qb][db][4 * i4 + 1] * inv);
-          w2.y = cvt_pk_bf16(acc[qb][db][4 * i4 + 2] * inv, acc[qb][db][4 * i4 + 3] * inv);
+          const float* a = accv + 16 * (NDB * qb + db) + 4 * i4;
+          w2.x = cvt_pk_bf16(a[0] * inv, a[1] * inv);
+          w2.y = cvt_pk_bf16(a[2] * inv, a[3] * inv);
           *reinterpret_cast<v2u*>(op + 8 * i4) = w2;
         }
       }
@@ -427,29 +632,19 @@ __global__ __launch_bounds__(WAVES * 64, (NQB == 1 ? 2 : 1)) void attend_dense_b
   }
 }
 
-// Four waves per workgroup, one 32-query block each; two workgroups per compute unit (two waves per SIMD).
-#ifndef DLLM_DENSE_QB
-#define DLLM_DENSE_QB 1
-#endif
-#ifndef DLLM_DENSE_WAVES
-#define DLLM_DENSE_WAVES 4
-#endif
-constexpr int kDenseQB = DLLM_DENSE_QB, kDenseWaves = DLLM_DENSE_WAVES;
-
 hipError_t launch_attend_dense_bf16(const Shape& s, const void* q, const void* k, const void* v,
                                     const int32_t* cu_q, const int32_t* cu_kv, const uint8_t* seq_mode, int which,
                                     void* o, hipStream_t st) {
-  constexpr int rows = kDenseWaves * 32 * kDenseQB;
   if (s.max_q == 0) return hipSuccess;   // no sequence has a query: nothing to write
-  dim3 grid((s.max_q + rows - 1) / rows, s.hq, s.batch);
+  dim3 grid((s.max_q + kDenseRows - 1) / kDenseRows, s.hq, s.batch);
   const uint16_t *qh = static_cast<const uint16_t*>(q), *kh = static_cast<const uint16_t*>(k),
                  *vh = static_cast<const uint16_t*>(v);
   if (s.d == 128)
-    attend_dense_bf16_kernel<128, kDenseQB, kDenseWaves><<<grid, kDenseWaves * 64, 0, st>>>(
-        qh, kh, vh, cu_q, cu_kv, seq_mode, which, static_cast<uint16_t*>(o), s);
+    attend_dense_bf16_kernel<128><<<grid, kDenseWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, seq_mode, which,
+                                                                     static_cast<uint16_t*>(o), s);
   else
-    attend_dense_bf16_kernel<64, kDenseQB, kDenseWaves><<<grid, kDenseWaves * 64, 0, st>>>(
-        qh, kh, vh, cu_q, cu_kv, seq_mode, which, static_cast<uint16_t*>(o), s);
+    attend_dense_bf16_kernel<64><<<grid, kDenseWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, seq_mode, which,
+                                                                    static_cast<uint16_t*>(o), s);
   return hipGetLastError();
 }
 

@@ -94,7 +94,7 @@ __device__ __forceinline__ void load16_to_lds(const void* src, uint32_t lds_wave
       "global_load_lds_dwordx4 %0, off"
       :
       : "v"(src), "s"(lds_wave_base)
-      : "memory");   // m0 is not tracked by the compiler as an allocatable register; nothing else in these kernels uses it
+      : "memory", "m0");
 }
 // Same, with the global address given as a wave-uniform base plus a 32-bit per-lane byte offset (no
 // vector arithmetic on 64-bit addresses).
@@ -105,7 +105,30 @@ __device__ __forceinline__ void load16_to_lds(const void* uniform_base, uint32_t
       "global_load_lds_dwordx4 %0, %1"
       :
       : "v"(lane_off), "s"(uniform_base), "s"(lds_wave_base)
-      : "memory");
+      : "memory", "m0");
+}
+// The same two with the LDS address given as a base that stays in one scalar register plus a
+// compile-time byte offset, added on the way into m0 (so that an unrolled loop does not keep one
+// scalar register per LDS destination).
+template <int kLdsOff>
+__device__ __forceinline__ void load16_to_lds(const void* src, uint32_t lds_wave_base) {
+  asm volatile(
+      "s_add_u32 m0, %1, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, off"
+      :
+      : "v"(src), "s"(lds_wave_base), "n"(kLdsOff)
+      : "memory", "m0", "scc");
+}
+template <int kLdsOff>
+__device__ __forceinline__ void load16_to_lds(const void* uniform_base, uint32_t lane_off, uint32_t lds_wave_base) {
+  asm volatile(
+      "s_add_u32 m0, %2, %3\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(lane_off), "s"(uniform_base), "s"(lds_wave_base), "n"(kLdsOff)
+      : "memory", "m0", "scc");
 }
 // Four bytes per lane: lane l's dword lands at LDS byte address lds_wave_base + 4 * l.
 __device__ __forceinline__ void load4_to_lds(const void* src, uint32_t lds_wave_base) {
@@ -115,7 +138,7 @@ __device__ __forceinline__ void load4_to_lds(const void* src, uint32_t lds_wave_
       "global_load_lds_dword %0, off"
       :
       : "v"(src), "s"(lds_wave_base)
-      : "memory");
+      : "memory", "m0");
 }
 // Waits until every load16_to_lds / load4_to_lds this wave has issued has written its LDS bytes.
 __device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

@@ -200,3 +200,13 @@ def test_python_struct_matches_the_header_layout(tmp_path):
     assert int(out["sizeof"]) == ctypes.sizeof(hcsa.DllmBatch)
     for f in fields:
         assert int(out[f]) == getattr(hcsa.DllmBatch, f).offset, f
+
+
+def test_generated_dense_step_text_is_current(tmp_path):
+    """csrc/attend_dense_step.inc is generated by csrc/gen_dense_step.py and committed: the two must agree."""
+    import subprocess
+    import sys
+    csrc = os.path.join(ROOT, "paper_2512_17077_amd", "csrc")
+    subprocess.run([sys.executable, os.path.join(csrc, "gen_dense_step.py"), f"--out={tmp_path}"], check=True,
+                   capture_output=True)
+    assert open(tmp_path / "attend_dense_step.inc").read() == open(os.path.join(csrc, "attend_dense_step.inc")).read()
