@@ -38,9 +38,11 @@
  *              total_* and max_* are host-side scalars.
  *   Errors     A negative dllm_status is returned and dllm_last_error() describes it.  All argument
  *              checks are made on the host from scalars and pointer nullness; a failed check launches
- *              nothing.  Not checked (undefined behaviour if violated): cu_* non-decreasing and
- *              starting at 0, max_* really bounding the per-sequence values, 0 <= k_b <= L_b, and
- *              idx entries inside [0, L_b).  NaN inputs are unsupported.
+ *              nothing.  Not checked by the release library (undefined behaviour if violated): cu_*
+ *              non-decreasing, starting at 0 and ending at total_*, max_* really bounding the
+ *              per-sequence values, 0 <= k_b <= L_b, and idx entries inside [0, L_b).  A library built
+ *              with -DDLLM_CHECK_PRECONDITIONS checks all of these on the device before anything
+ *              depends on them (see dllm_hcsa_precondition_errors).  NaN inputs are unsupported.
  */
 #ifndef DLLM_HCSA_H
 #define DLLM_HCSA_H
@@ -166,7 +168,8 @@ dllm_status dllm_hcsa_select_static(const dllm_batch *batch,
  * (k_b == 0 sparse, or L_b == 0 dense) gets zeros.  Scores, softmax state and accumulators are
  * fp32; bf16 inputs are multiplied on the matrix cores, fp32 inputs with fp32 arithmetic.
  *
- * seq_mode may be NULL (all sparse).  cu_k may be NULL only if total_k == 0.  idx == NULL with
+ * seq_mode may be NULL (all sparse).  cu_k may be NULL only if total_k == 0; every sequence not flagged
+ * dense then counts as keeping nothing and gets zeros.  idx == NULL with
  * total_k > 0 means the identity lists: sparse sequence b attends over its rows 0 .. k_b-1 in order
  * (k_b from cu_k), which is how a packed cache written by dllm_hcsa_pack is read.
  * max_k bounds k_b over sparse sequences (0 allowed when there are none).
@@ -210,6 +213,22 @@ size_t dllm_dense_refresh_attend_workspace(const dllm_batch *batch);
 dllm_status dllm_dense_refresh_attend(const dllm_batch *batch,
                                       void *o, /* device, [total_q, n_q_heads, head_dim] */
                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Device-side precondition checks (debug aid).  In a library built with -DDLLM_CHECK_PRECONDITIONS
+ * every entry point above first verifies, on the device, the conditions the release library leaves to
+ * the caller, and sets bits in one error word per GPU; when a bit is set, every kernel of the call, and
+ * of later calls, returns without reading or writing anything, so a violating input cannot fault.  This
+ * function waits for hip_stream, stores the word in *errors_out (host memory) and clears it.  In the
+ * release library nothing is checked: it stores 0 and returns DLLM_ERR_UNSUPPORTED.
+ */
+#define DLLM_CHECK_CU_Q 1u      /* cu_q: not starting at 0, decreasing, a sequence above max_q, or not ending at total_q */
+#define DLLM_CHECK_CU_KV 2u     /* the same for cu_kv, max_kv, total_kv */
+#define DLLM_CHECK_CU_K 4u      /* the same for cu_k, max_k, total_k */
+#define DLLM_CHECK_K_OVER_L 8u  /* a sparse sequence keeps more rows than it has */
+#define DLLM_CHECK_FORCED 16u   /* a sequence with kept rows keeps, or has, fewer than forced_tail rows */
+#define DLLM_CHECK_IDX 32u      /* an index outside [0, L_b) in a sparse sequence's list */
+dllm_status dllm_hcsa_precondition_errors(void *hip_stream, uint32_t *errors_out /* host */);
 
 /* Text of the calling thread's most recent error ("" if none); static storage, never NULL. */
 const char *dllm_last_error(void);

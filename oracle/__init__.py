@@ -23,14 +23,37 @@ _OVERRIDE = os.environ.get("HCSA_ORACLE_LIB_OVERRIDE")
 F32, BF16 = 0, 1
 
 
-def build(force: bool = False) -> str:
+def build(force: bool = False, sanitize: bool = False, out: str | None = None) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off keeps every fp32 step of
-    the score a separately rounded operation; fmaf comes from libm."""
+    the score a separately rounded operation; fmaf comes from libm.
+
+    sanitize=True builds a second library (libhcsa_oracle_san.so, or `out`) with
+    -fsanitize=address,undefined for running the pin suite under the sanitizers; a process that loads
+    it must have the AddressSanitizer runtime preloaded (see sanitizer_env())."""
+    if sanitize:
+        lib = out or os.path.join(_HERE, "libhcsa_oracle_san.so")
+        cmd = ["gcc", "-O1", "-g", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+               "-Wall", "-Wextra", "-o", lib, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+        return lib
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
                "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
+
+
+def sanitizer_env(lib: str) -> dict:
+    """Environment for a child process that loads the sanitized build `lib` in place of the oracle:
+    the AddressSanitizer runtime has to be the first library of the process, so it is preloaded (ahead of
+    whatever is preloaded already); leak checking is off because the Python interpreter itself never
+    frees everything."""
+    asan = subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True).stdout.strip()
+    env = dict(os.environ, HCSA_ORACLE_LIB_OVERRIDE=lib, ASAN_OPTIONS="detect_leaks=0:abort_on_error=1",
+               UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    env["LD_PRELOAD"] = asan + ((":" + os.environ["LD_PRELOAD"]) if os.environ.get("LD_PRELOAD") else "")
+    return env
 
 
 def _load():

@@ -19,8 +19,11 @@ INCLUDE = os.path.join(_ROOT, "include")
 BUILD_DIR = os.path.join(_HERE, "_build")
 LIB_PATH = os.path.join(_HERE, "libdllm_hcsa.so")
 
-SOURCES = ["api.hip", "select_kernels.hip", "pack_kernels.hip", "attend_f32.hip", "attend_sparse_bf16.hip",
-           "attend_dense_bf16.hip"]
+SOURCES = ["api.hip", "checks.hip", "select_kernels.hip", "pack_kernels.hip", "attend_f32.hip",
+           "attend_sparse_bf16.hip", "attend_dense_bf16.hip"]
+# the same sources with the device-side precondition checks compiled in (a debugging aid, see include/dllm_hcsa.h)
+LIB_PATH_CHECKED = os.path.join(_HERE, "libdllm_hcsa_checked.so")
+CHECKED_FLAGS = ["-DDLLM_CHECK_PRECONDITIONS"]
 
 # packed-fp32 VALU forms are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
@@ -35,8 +38,9 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found; libdllm_hcsa.so cannot be built")
 
 
-def _compile(src: str, extra=()) -> str:
-    obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, extra=(), subdir: str = "") -> str:
+    os.makedirs(os.path.join(BUILD_DIR, subdir), exist_ok=True)
+    obj = os.path.join(BUILD_DIR, subdir, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
@@ -48,14 +52,20 @@ def _compile(src: str, extra=()) -> str:
     return obj
 
 
-def build(verbose: bool = False, extra=()) -> str:
+def build(verbose: bool = False, extra=(), checked: bool = True) -> str:
+    """Compiles the library, and (checked=True) its twin with the precondition checks, always from scratch."""
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
-    subprocess.run(cmd, check=True)
-    if verbose:
-        print("built", LIB_PATH)
+    jobs = [(s, tuple(extra), "") for s in SOURCES]
+    if checked:
+        jobs += [(s, tuple(extra) + tuple(CHECKED_FLAGS), "checked") for s in SOURCES]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(lambda j: _compile(*j), jobs))
+    n = len(SOURCES)
+    for lib, part in ((LIB_PATH, objs[:n]), (LIB_PATH_CHECKED, objs[n:])):
+        if part:
+            subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *part], check=True)
+            if verbose:
+                print("built", lib)
     return LIB_PATH
 
 

@@ -86,9 +86,9 @@ dllm_status check_dense_strides(const dllm_batch* b) {
 dllm_status check_sparse_strides(const dllm_batch* b) {
   if (b->dtype != DLLM_BF16) return DLLM_OK;
   const int64_t pitch = b->kv_stride_tok * 2;
-  if (pitch >= (int64_t(1) << 24) || int64_t(b->max_kv) * pitch >= (int64_t(1) << 32))
+  if (pitch >= (int64_t(1) << 24) || b->max_kv > (1 << 24) || int64_t(b->max_kv) * pitch >= (int64_t(1) << 32))
     return fail(DLLM_ERR_UNSUPPORTED,
-                "one sequence's K/V rows must span < 4 GiB with a token stride < 16 MiB for the bf16 gather kernel "
+                "one sequence must have at most 2^24 K/V rows spanning < 4 GiB with a token stride < 16 MiB for the bf16 gather kernel "
                 "(max_kv=%d, kv_stride_tok=%lld)", b->max_kv, static_cast<long long>(b->kv_stride_tok));
   return DLLM_OK;
 }
@@ -213,10 +213,13 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch* batch, const int32_t* cu_k, in
   if (st != DLLM_OK) return st;
   if ((st = check_workspace(workspace, workspace_bytes, dllm::plan_select(s).bytes)) != DLLM_OK) return st;
   g_err[0] = 0;
-  return device_result(dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k,
-                                           total_k, max_k, pool_w, forced_tail, head_sum, idx_out, workspace,
-                                           static_cast<hipStream_t>(hip_stream)),
-                       "dllm_hcsa_select");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = dllm::validate_inputs(s, batch->cu_q, batch->cu_kv, cu_k, nullptr, nullptr, total_k, max_k, forced_tail,
+                                       stream);
+  if (e == hipSuccess)
+    e = dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k, total_k, max_k, pool_w,
+                            forced_tail, head_sum, idx_out, workspace, stream);
+  return device_result(e, "dllm_hcsa_select");
 }
 
 dllm_status dllm_hcsa_select_static(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
@@ -233,10 +236,13 @@ dllm_status dllm_hcsa_select_static(const dllm_batch* batch, const int32_t* cu_k
   void* ws = nullptr;
   if ((st = scratch_of_current_device(&ws)) != DLLM_OK) return st;
   g_err[0] = 0;
-  return device_result(dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k,
-                                           total_k, max_k, pool_w, forced_tail, head_sum, idx_out, ws,
-                                           static_cast<hipStream_t>(hip_stream)),
-                       "dllm_hcsa_select_static");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = dllm::validate_inputs(s, batch->cu_q, batch->cu_kv, cu_k, nullptr, nullptr, total_k, max_k, forced_tail,
+                                       stream);
+  if (e == hipSuccess)
+    e = dllm::launch_select(s, batch->dtype, batch->q, batch->k, batch->cu_q, batch->cu_kv, cu_k, total_k, max_k, pool_w,
+                            forced_tail, head_sum, idx_out, ws, stream);
+  return device_result(e, "dllm_hcsa_select_static");
 }
 
 dllm_status dllm_hcsa_select(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
@@ -263,15 +269,19 @@ dllm_status dllm_hcsa_attend(const dllm_batch* batch, const int32_t* idx, const 
   if (total_k < 0 || max_k < 0 || max_k > total_k || max_k > batch->max_kv)
     return fail(DLLM_ERR_INVALID_ARG, "need 0 <= max_k <= min(total_k, max_kv) (got max_k=%d, total_k=%d, max_kv=%d)",
                 max_k, total_k, batch->max_kv);
-  if (cu_k == nullptr && (total_k > 0 || seq_mode == nullptr))
-    return fail(DLLM_ERR_INVALID_ARG, "cu_k may be NULL only when every sequence is flagged dense");
+  if (cu_k == nullptr && total_k > 0)
+    return fail(DLLM_ERR_INVALID_ARG, "cu_k may be NULL only when total_k is 0 (got total_k=%d)", total_k);
   if (seq_mode != nullptr && (st = check_dense_strides(batch)) != DLLM_OK) return st;
   if (total_k > 0 && (st = check_sparse_strides(batch)) != DLLM_OK) return st;
   const dllm::AttendPlan plan = dllm::plan_attend(s, batch->dtype, max_k);
   if ((st = check_workspace(workspace, workspace_bytes, plan.bytes)) != DLLM_OK) return st;
   g_err[0] = 0;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipError_t e = hipSuccess;
+  hipError_t e = dllm::validate_inputs(s, batch->cu_q, batch->cu_kv, cu_k, idx, seq_mode, total_k, max_k, 0, stream);
+  // Without cu_k nothing is kept anywhere: every sequence not flagged dense gets zeros.
+  if (e == hipSuccess && cu_k == nullptr)
+    e = dllm::launch_zero_sparse_outputs(s, batch->dtype, batch->cu_q, seq_mode, o, stream);
+  if (e != hipSuccess) return device_result(e, "dllm_hcsa_attend");
   if (batch->dtype == DLLM_F32) {
     if (cu_k != nullptr)
       e = dllm::launch_attend_f32(s, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, idx, cu_k, total_k,
@@ -304,9 +314,12 @@ dllm_status dllm_hcsa_pack(const dllm_batch* batch, const int32_t* idx, const in
     return fail(DLLM_ERR_INVALID_ARG, "need 1 <= max_k <= min(total_k, max_kv) (got max_k=%d, total_k=%d, max_kv=%d)",
                 max_k, total_k, batch->max_kv);
   g_err[0] = 0;
-  return device_result(dllm::launch_pack(s, batch->dtype, batch->k, batch->v, batch->cu_kv, idx, cu_k, total_k, max_k,
-                                         k_packed, v_packed, static_cast<hipStream_t>(hip_stream)),
-                       "dllm_hcsa_pack");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = dllm::validate_inputs(s, batch->cu_q, batch->cu_kv, cu_k, idx, nullptr, total_k, max_k, 0, stream);
+  if (e == hipSuccess)
+    e = dllm::launch_pack(s, batch->dtype, batch->k, batch->v, batch->cu_kv, idx, cu_k, total_k, max_k, k_packed,
+                          v_packed, stream);
+  return device_result(e, "dllm_hcsa_pack");
 }
 
 size_t dllm_dense_refresh_attend_workspace(const dllm_batch* batch) {
@@ -326,7 +339,8 @@ dllm_status dllm_dense_refresh_attend(const dllm_batch* batch, void* o, void* wo
   if ((st = check_dense_strides(batch)) != DLLM_OK) return st;
   g_err[0] = 0;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipError_t e;
+  hipError_t e = dllm::validate_inputs(s, batch->cu_q, batch->cu_kv, nullptr, nullptr, nullptr, 0, 0, 0, stream);
+  if (e != hipSuccess) return device_result(e, "dllm_dense_refresh_attend");
   if (batch->dtype == DLLM_F32)
     e = dllm::launch_attend_f32(s, batch->q, batch->k, batch->v, batch->cu_q, batch->cu_kv, nullptr, nullptr, 0,
                                 nullptr, 2, o, stream);

@@ -249,7 +249,8 @@ template <int D>
 __global__ __launch_bounds__(kDenseWaves * 64, 1) void attend_dense_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const uint8_t* __restrict__ seq_mode,
-    int which, uint16_t* __restrict__ o, Shape s) {
+    int which, uint16_t* __restrict__ o, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   constexpr int NQB = kDenseQB;
   constexpr int CH = D / 8;
   constexpr int ROWB = 2 * D;
@@ -641,10 +642,10 @@ hipError_t launch_attend_dense_bf16(const Shape& s, const void* q, const void* k
                  *vh = static_cast<const uint16_t*>(v);
   if (s.d == 128)
     attend_dense_bf16_kernel<128><<<grid, kDenseWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, seq_mode, which,
-                                                                     static_cast<uint16_t*>(o), s);
+                                                                     static_cast<uint16_t*>(o), s DLLM_CHECK_PASS);
   else
     attend_dense_bf16_kernel<64><<<grid, kDenseWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, seq_mode, which,
-                                                                    static_cast<uint16_t*>(o), s);
+                                                                    static_cast<uint16_t*>(o), s DLLM_CHECK_PASS);
   return hipGetLastError();
 }
 

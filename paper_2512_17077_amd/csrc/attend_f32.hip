@@ -26,7 +26,8 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cu_k, int32_t total_k, const uint8_t* __restrict__ seq_mode, int which,
-    float* __restrict__ o, Shape s) {
+    float* __restrict__ o, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   const int b = blockIdx.z, h = blockIdx.y;
   const bool flagged_dense = seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE;
   if (which == 0 && flagged_dense) return;
@@ -99,6 +100,29 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(
   for (int u = 0; u < NO; ++u) op[lane + 64 * u] = acc[u] * inv;
 }
 
+// o rows of the sequences not flagged dense := 0 (what attention over an empty kept list is defined as);
+// used when a call passes no cu_k at all.  es: element bytes.
+__global__ __launch_bounds__(256) void zero_sparse_outputs_kernel(const int32_t* __restrict__ cu_q,
+                                                                  const uint8_t* __restrict__ seq_mode,
+                                                                  char* __restrict__ o, int row_bytes DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
+  const int b = blockIdx.y;
+  if (seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE) return;
+  const int64_t lo = int64_t(cu_q[b]) * row_bytes, hi = int64_t(cu_q[b + 1]) * row_bytes;   // multiples of 16
+  for (int64_t e = lo + (int64_t(blockIdx.x) * 256 + threadIdx.x) * 16; e < hi; e += int64_t(gridDim.x) * 256 * 16)
+    *reinterpret_cast<v4u*>(o + e) = v4u{0u, 0u, 0u, 0u};
+}
+
+hipError_t launch_zero_sparse_outputs(const Shape& s, dllm_dtype dt, const int32_t* cu_q, const uint8_t* seq_mode,
+                                      void* o, hipStream_t st) {
+  if (s.max_q == 0) return hipSuccess;
+  const int row_bytes = s.hq * s.d * (dt == DLLM_F32 ? 4 : 2);
+  const int64_t per_seq = int64_t(s.max_q) * row_bytes / (256 * 16) + 1;
+  zero_sparse_outputs_kernel<<<dim3(unsigned(per_seq < 64 ? per_seq : 64), s.batch), 256, 0, st>>>(
+      cu_q, seq_mode, static_cast<char*>(o), row_bytes DLLM_CHECK_PASS);
+  return hipGetLastError();
+}
+
 hipError_t launch_attend_f32(const Shape& s, const void* q, const void* k, const void* v, const int32_t* cu_q,
                              const int32_t* cu_kv, const int32_t* idx, const int32_t* cu_k, int32_t total_k,
                              const uint8_t* seq_mode, int which, void* o, hipStream_t st) {
@@ -108,10 +132,10 @@ hipError_t launch_attend_f32(const Shape& s, const void* q, const void* k, const
               *vf = static_cast<const float*>(v);
   if (s.d == 128)
     attend_f32_kernel<128><<<grid, 256, 0, st>>>(qf, kf, vf, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, which,
-                                                static_cast<float*>(o), s);
+                                                static_cast<float*>(o), s DLLM_CHECK_PASS);
   else
     attend_f32_kernel<64><<<grid, 256, 0, st>>>(qf, kf, vf, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, which,
-                                               static_cast<float*>(o), s);
+                                               static_cast<float*>(o), s DLLM_CHECK_PASS);
   return hipGetLastError();
 }
 

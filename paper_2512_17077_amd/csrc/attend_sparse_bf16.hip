@@ -199,7 +199,8 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cu_k, int32_t total_k, const uint8_t* __restrict__ seq_mode,
     uint16_t* __restrict__ o, float* __restrict__ po, float* __restrict__ pm, float* __restrict__ pl,
-    int32_t chunk_rows, int ranked, Shape s) {
+    int32_t chunk_rows, int ranked, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   constexpr int CH = D / 8;             // 16-byte chunks per row
   constexpr int ROWB = 2 * D;
   constexpr int TILEB = kTile * ROWB;
@@ -434,7 +435,8 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ idx,
     const int32_t* __restrict__ cu_k, int32_t total_k, const uint8_t* __restrict__ seq_mode,
     uint16_t* __restrict__ o, float* __restrict__ po, float* __restrict__ pm, float* __restrict__ pl,
-    int32_t chunk_rows, int32_t n_chunks, int32_t n_wg, Shape s) {
+    int32_t chunk_rows, int32_t n_chunks, int32_t n_wg, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   constexpr int WAVES = kWavesMulti;   // n_wg: the size of the grid, as an argument like the others
   constexpr int CH = D / 8;
   constexpr int ROWB = 2 * D;
@@ -675,7 +677,8 @@ template <int D>
 __global__ __launch_bounds__(256) void attend_sparse_combine_kernel(
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_k, const uint8_t* __restrict__ seq_mode,
     const float* __restrict__ po, const float* __restrict__ pm, const float* __restrict__ pl,
-    uint16_t* __restrict__ o, int32_t chunk_rows, Shape s) {
+    uint16_t* __restrict__ o, int32_t chunk_rows, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   const int h = blockIdx.x, b = blockIdx.y;
   if (seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE) return;
   const int kb = cu_k[b + 1] - cu_k[b];
@@ -735,28 +738,28 @@ hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const 
   if (multi) {
     if (s.d == 128)
       attend_sparse_multi_bf16_kernel<128><<<n_cu, kWavesMulti * 64, 0, st>>>(
-          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s);
+          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s DLLM_CHECK_PASS);
     else
       attend_sparse_multi_bf16_kernel<64><<<n_cu, kWavesMulti * 64, 0, st>>>(
-          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s);
+          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s DLLM_CHECK_PASS);
   } else {
     dim3 grid(p.n_chunks, s.hq, s.batch);
     // the start order only matters when the workgroups cannot all be resident at once (two per compute unit)
     const int ranked = n_items > 512 ? 1 : 0;
     if (s.d == 128)
       attend_sparse_bf16_kernel<128><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
-                                                                  seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
+                                                                  seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s DLLM_CHECK_PASS);
     else
       attend_sparse_bf16_kernel<64><<<grid, kWaves * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k,
-                                                                 seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s);
+                                                                 seq_mode, oh, po, pm, pl, p.chunk_rows, ranked, s DLLM_CHECK_PASS);
   }
   e = hipGetLastError();
   if (e != hipSuccess || p.n_chunks <= 1) return e;
   dim3 cgrid(s.hq, s.batch);
   if (s.d == 128)
-    attend_sparse_combine_kernel<128><<<cgrid, 256, 0, st>>>(cu_q, cu_k, seq_mode, po, pm, pl, oh, p.chunk_rows, s);
+    attend_sparse_combine_kernel<128><<<cgrid, 256, 0, st>>>(cu_q, cu_k, seq_mode, po, pm, pl, oh, p.chunk_rows, s DLLM_CHECK_PASS);
   else
-    attend_sparse_combine_kernel<64><<<cgrid, 256, 0, st>>>(cu_q, cu_k, seq_mode, po, pm, pl, oh, p.chunk_rows, s);
+    attend_sparse_combine_kernel<64><<<cgrid, 256, 0, st>>>(cu_q, cu_k, seq_mode, po, pm, pl, oh, p.chunk_rows, s DLLM_CHECK_PASS);
   return hipGetLastError();
 }
 

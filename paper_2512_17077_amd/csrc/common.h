@@ -53,6 +53,8 @@ AttendPlan plan_attend(const Shape& s, dllm_dtype dt, int32_t max_k);
 hipError_t launch_attend_f32(const Shape& s, const void* q, const void* k, const void* v, const int32_t* cu_q,
                              const int32_t* cu_kv, const int32_t* idx, const int32_t* cu_k, int32_t total_k,
                              const uint8_t* seq_mode, int which, void* o, hipStream_t st);
+hipError_t launch_zero_sparse_outputs(const Shape& s, dllm_dtype dt, const int32_t* cu_q, const uint8_t* seq_mode,
+                                      void* o, hipStream_t st);
 hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const void* q, const void* k,
                                      const void* v, const int32_t* cu_q, const int32_t* cu_kv, const int32_t* idx,
                                      const int32_t* cu_k, int32_t total_k, const uint8_t* seq_mode, void* o,
@@ -60,6 +62,26 @@ hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const 
 hipError_t launch_attend_dense_bf16(const Shape& s, const void* q, const void* k, const void* v,
                                     const int32_t* cu_q, const int32_t* cu_kv, const uint8_t* seq_mode, int which,
                                     void* o, hipStream_t st);
+
+// ---- optional device-side precondition checks (checks.hip; built with -DDLLM_CHECK_PRECONDITIONS)
+// In that build every entry point first runs validators over the offset arrays and the index lists, which
+// set bits in an error word, and every kernel takes that word's address as its last argument and returns
+// at once if it is not zero: a violating input is reported and nothing is read or written through it.
+#ifdef DLLM_CHECK_PRECONDITIONS
+#define DLLM_CHECK_PARAM , const uint32_t* __restrict__ check_word
+#define DLLM_CHECK_PASS , dllm::check_word()
+#define DLLM_CHECK_EXIT() \
+  if (*check_word != 0) return
+uint32_t* check_word();   // device address of the current GPU's error word; NULL if it cannot be had
+#else
+#define DLLM_CHECK_PARAM
+#define DLLM_CHECK_PASS
+#define DLLM_CHECK_EXIT()
+#endif
+// Runs the validators (a no-op in the release build).  cu_k, idx and seq_mode may be NULL.
+hipError_t validate_inputs(const Shape& s, const int32_t* cu_q, const int32_t* cu_kv, const int32_t* cu_k,
+                           const int32_t* idx, const uint8_t* seq_mode, int32_t total_k, int32_t max_k,
+                           int32_t forced_tail, hipStream_t st);
 
 // ---- device helpers
 // 16-byte load of data that is read once per launch (K/V rows streamed or gathered from HBM): the

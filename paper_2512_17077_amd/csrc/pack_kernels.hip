@@ -22,7 +22,8 @@ template <int CH>
 __global__ __launch_bounds__(kPackThreads) void pack_kernel(
     const char* __restrict__ k, const char* __restrict__ v, const int32_t* __restrict__ cu_kv,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cu_k, int32_t total_k, char* __restrict__ kp,
-    char* __restrict__ vp, int es, Shape s) {
+    char* __restrict__ vp, int es, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   constexpr int ROWS = kPackThreads / CH;                 // rows per pass of the workgroup
   constexpr int ROWS_PER_WG = ROWS * kPackInFlight;
   const int h = blockIdx.y, b = blockIdx.z;
@@ -68,11 +69,11 @@ hipError_t launch_pack(const Shape& s, dllm_dtype dt, const void* k, const void*
   const char *kc = static_cast<const char*>(k), *vc = static_cast<const char*>(v);
   char *kpc = static_cast<char*>(kp), *vpc = static_cast<char*>(vp);
   if (ch == 8)
-    pack_kernel<8><<<grid, kPackThreads, 0, st>>>(kc, vc, cu_kv, idx, cu_k, total_k, kpc, vpc, es, s);
+    pack_kernel<8><<<grid, kPackThreads, 0, st>>>(kc, vc, cu_kv, idx, cu_k, total_k, kpc, vpc, es, s DLLM_CHECK_PASS);
   else if (ch == 16)
-    pack_kernel<16><<<grid, kPackThreads, 0, st>>>(kc, vc, cu_kv, idx, cu_k, total_k, kpc, vpc, es, s);
+    pack_kernel<16><<<grid, kPackThreads, 0, st>>>(kc, vc, cu_kv, idx, cu_k, total_k, kpc, vpc, es, s DLLM_CHECK_PASS);
   else
-    pack_kernel<32><<<grid, kPackThreads, 0, st>>>(kc, vc, cu_kv, idx, cu_k, total_k, kpc, vpc, es, s);
+    pack_kernel<32><<<grid, kPackThreads, 0, st>>>(kc, vc, cu_kv, idx, cu_k, total_k, kpc, vpc, es, s DLLM_CHECK_PASS);
   return hipGetLastError();
 }
 

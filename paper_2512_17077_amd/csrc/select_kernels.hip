@@ -80,7 +80,8 @@ template <int ES, int D, int GT>
 __global__ __launch_bounds__(kScoreWaves * 64, (ES * D <= 256 ? 2 : 1)) void score_kernel(
     const char* __restrict__ k, const char* __restrict__ q, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k, float* __restrict__ scores,
-    int tiles_per_wave, Shape s) {
+    int tiles_per_wave, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   constexpr int ROWB = D * ES;
   constexpr int CH = ROWB / 16;   // 16-byte chunks per row
   constexpr int EPC = 16 / ES;    // elements per chunk
@@ -216,7 +217,8 @@ __global__ __launch_bounds__(256) void head_sum_kernel(const float* __restrict__
                                                        const int32_t* __restrict__ cu_kv,
                                                        const int32_t* __restrict__ cu_k, int32_t total_kv,
                                                        int32_t pool_w, int32_t forced_tail, int32_t n_heads,
-                                                       float* __restrict__ summed) {
+                                                       float* __restrict__ summed DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   const int b = blockIdx.y;
   if (cu_k[b + 1] == cu_k[b]) return;
   const int kv0 = cu_kv[b];
@@ -272,7 +274,8 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k,
     int32_t total_kv, int32_t total_k, int32_t pool_w, int32_t lpad, int32_t forced_tail, int32_t head_sum,
-    int32_t n_heads, int32_t* __restrict__ idx_out) {
+    int32_t n_heads, int32_t* __restrict__ idx_out DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   extern __shared__ uint32_t dyn[];
   __shared__ uint32_t hist[256];
   // The leading byte of a score (sign and seven exponent bits) takes only a handful of values, and LDS
@@ -457,7 +460,8 @@ template <int R, int T>
 __global__ __launch_bounds__(T) void topk_reg_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k,
     int32_t total_kv, int32_t total_k, int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t n_heads,
-    int32_t* __restrict__ idx_out) {
+    int32_t* __restrict__ idx_out DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
   constexpr int kCopies = 16, kWaves = T / 64;
   constexpr int E = R * kWaves / 64;   // (round, wave) counts per lane in the final scan
   static_assert(T >= 256 && R * kWaves % 64 == 0 && (E == 1 || E == 2), "one or two counts per lane");
@@ -630,7 +634,7 @@ static hipError_t launch_score(const Shape& s, const void* k, const void* q, con
     const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, int(sums_bytes));
     if (ea != hipSuccess) return ea;
-    kernel<<<grid, block, sums_bytes, st>>>(kp, qp, cu_q, cu_kv, cu_k, scores, tpw, s);
+    kernel<<<grid, block, sums_bytes, st>>>(kp, qp, cu_q, cu_kv, cu_k, scores, tpw, s DLLM_CHECK_PASS);
     return hipGetLastError();
   };
   if (s.group % 4 == 0) return launch(score_kernel<ES, D, 4>);
@@ -658,7 +662,7 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
   if (head_sum) {   // sum (pooled) scores over the heads first; the top-k then ranks one plain row per sequence
     float* summed = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_summed);
     head_sum_kernel<<<dim3((s.max_kv + 255) / 256, s.batch), 256, 0, st>>>(scores, cu_kv, cu_k, s.total_kv, pool_w,
-                                                                           forced_tail, s.hq, summed);
+                                                                           forced_tail, s.hq, summed DLLM_CHECK_PASS);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     ranked = summed;
     pool_w = 1;
@@ -670,7 +674,7 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
     // kernel below on the mixed workload, 20.5 against 18.1 us, although each workgroup took less time:
     // they did not all run at once.  Thirty-two per thread in four waves took 25 us.)
     topk_reg_kernel<8, kTopkThreads><<<grid, kTopkThreads, pool_w == 1 ? 0 : size_t(lpad) * 4, st>>>(
-        ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, forced_tail, head_sum, s.hq, idx_out);
+        ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, forced_tail, head_sum, s.hq, idx_out DLLM_CHECK_PASS);
     return hipGetLastError();
   }
   const size_t lds = size_t(lpad) * 4 * (pool_w == 1 ? 1 : 2);
@@ -680,7 +684,7 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
     if (e != hipSuccess) return e;
   }
   topk_kernel<<<grid, kTopkThreads, lds, st>>>(
-      ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, lpad, forced_tail, head_sum, s.hq, idx_out);
+      ranked, cu_kv, cu_k, s.total_kv, total_k, pool_w, lpad, forced_tail, head_sum, s.hq, idx_out DLLM_CHECK_PASS);
   return hipGetLastError();
 }
 

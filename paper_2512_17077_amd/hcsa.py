@@ -15,6 +15,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdllm_hcsa.so")
+LIB_PATH_CHECKED = os.path.join(_HERE, "libdllm_hcsa_checked.so")   # built with the device-side precondition checks
 
 DLLM_OK = 0
 DLLM_ERR_INVALID_ARG = -1
@@ -28,9 +29,10 @@ EXPORTS = [
     "dllm_hcsa_select_workspace", "dllm_hcsa_select", "dllm_hcsa_select_ex", "dllm_hcsa_select_static",
     "dllm_hcsa_attend_workspace", "dllm_hcsa_attend",
     "dllm_dense_refresh_attend_workspace", "dllm_dense_refresh_attend",
-    "dllm_hcsa_pack",
+    "dllm_hcsa_pack", "dllm_hcsa_precondition_errors",
     "dllm_last_error", "dllm_hcsa_version",
 ]
+DLLM_CHECK_CU_Q, DLLM_CHECK_CU_KV, DLLM_CHECK_CU_K, DLLM_CHECK_K_OVER_L, DLLM_CHECK_FORCED, DLLM_CHECK_IDX = 1, 2, 4, 8, 16, 32
 
 
 class DllmBatch(ctypes.Structure):
@@ -95,12 +97,29 @@ def lib() -> ctypes.CDLL:
         L.dllm_dense_refresh_attend.argtypes = [P, vp, vp, sz, vp]
         L.dllm_hcsa_pack.restype = ctypes.c_int
         L.dllm_hcsa_pack.argtypes = [P, vp, vp, i32, i32, vp, vp, vp]
+        L.dllm_hcsa_precondition_errors.restype = ctypes.c_int
+        L.dllm_hcsa_precondition_errors.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
         L.dllm_last_error.restype = ctypes.c_char_p
         L.dllm_last_error.argtypes = []
         L.dllm_hcsa_version.restype = i32
         L.dllm_hcsa_version.argtypes = []
         _lib = L
     return _lib
+
+
+def use_checked_library(on: bool = True):
+    """Switch this binding to the library built with the device-side precondition checks (or back).  The
+    checked library must have been built (paper_2512_17077_amd.build does both)."""
+    global _lib, LIB_PATH
+    _lib = None
+    LIB_PATH = LIB_PATH_CHECKED if on else os.path.join(_HERE, "libdllm_hcsa.so")
+
+
+def dllm_hcsa_precondition_errors(stream=None) -> int:
+    """Fetch and clear the error word of the checked library (raises DLLM_ERR_UNSUPPORTED in the release one)."""
+    out = ctypes.c_uint32(0)
+    _raise(lib().dllm_hcsa_precondition_errors(_stream(stream), ctypes.byref(out)))
+    return int(out.value)
 
 
 def last_error() -> str:

@@ -205,6 +205,19 @@ def subset(w: Workload, seqs, name: Optional[str] = None) -> Workload:
                     w.seq_mode[seqs].copy(), w.softmax_scale)
 
 
+def with_keep(w: Workload, keep, name: Optional[str] = None) -> Workload:
+    """The same batch with other per-sequence numbers of kept rows (tensors shared, offsets rebuilt)."""
+    keep = np.asarray(keep, dtype=np.int64)
+    assert len(keep) == w.batch and (keep <= w.kv_lens).all() and (keep >= 0).all()
+    return dataclasses.replace(w, name=name or w.name + "_rekept", cu_k=_prefix(keep), seq_mode=w.seq_mode.copy())
+
+
+def at_retention(w: Workload, ratio: float, name: Optional[str] = None) -> Workload:
+    """The same batch with every sparse sequence keeping `ratio` of its positions (Table 2's default is 0.5)."""
+    keep = [keep_count(ratio, l) if m == MODE_SPARSE else 0 for l, m in zip(w.kv_lens, w.seq_mode)]
+    return with_keep(w, keep, name or f"{w.name}_r{ratio:g}")
+
+
 def config(c: int, scale_down: int = 1) -> Workload:
     """The five benchmark workloads.  `scale_down` > 1 divides sequence lengths
     (configs 3-5) to get a same-structure case the CPU oracle finishes quickly."""

@@ -104,6 +104,30 @@ def test_attend_scalar_checks():
     assert attend_status(b, total_k=4000, max_k=4000, ws_bytes=need - 1) == hcsa.DLLM_ERR_WORKSPACE
 
 
+def test_attend_without_cu_k_needs_an_empty_kept_set():
+    b = good_batch()
+    assert attend_status(b, cu_k=None, total_k=1, max_k=0) == hcsa.DLLM_ERR_INVALID_ARG
+    assert "cu_k may be NULL only" in hcsa.last_error()
+    # idx may be NULL with cu_k present (identity lists); only the reverse is refused
+    assert attend_status(b, idx=None, ws=None, ws_bytes=0, total_k=100, max_k=301) == hcsa.DLLM_ERR_INVALID_ARG
+    assert "max_k" in hcsa.last_error()
+
+
+def test_gather_kernel_row_count_limit():
+    """One narrow KV head: 2^24 + 1 rows of 128 bytes stay below 4 GiB, but the row index no longer fits
+    the 24-bit multiply that forms the byte offset."""
+    b = good_batch()
+    b.n_q_heads = b.n_kv_heads = 1
+    b.head_dim = 64
+    b.q_stride_tok = b.q_stride_head = b.kv_stride_tok = b.kv_stride_head = 64
+    b.total_kv, b.max_kv = 1 << 25, (1 << 24) + 1
+    assert attend_status(b) == hcsa.DLLM_ERR_UNSUPPORTED
+    assert "2^24" in hcsa.last_error()
+    b.max_kv = 1 << 24
+    b.batch = 2
+    assert attend_status(b, ws=None, ws_bytes=0) in (hcsa.DLLM_ERR_WORKSPACE, hcsa.DLLM_ERR_DEVICE)   # past the shape checks
+
+
 def test_select_ex_option_checks():
     b = good_batch()
     L = hcsa.lib()

@@ -263,14 +263,24 @@ def test_attend_more_lists_than_compute_units(D):
 
 
 def test_attend_keep_all_equals_dense_entry_point():
+    """Keeping every row through the index lists and the dense entry point: both against the oracle's dense
+    attention (k = L reproduces dense softmax attention)."""
     w = custom(11, torch.bfloat16, 4, 2, 128, [333, 64], [32, 20], [333, 64])
     idx = oracle_select(w)
+    assert all(np.array_equal(idx[h, int(w.cu_k[b]):int(w.cu_k[b + 1])], np.arange(int(w.kv_lens[b])))
+               for h in range(4) for b in range(2))
+    dense_w = synth.with_keep(w, [0, 0])
+    dense_w.seq_mode[:] = 1
+    want = oracle_attend(dense_w, np.zeros((4, 0), np.int32))
     dw = hcsa.DeviceWorkload(w)
+    dw.o.fill_(float("nan"))
     dw.attend(torch.from_numpy(idx).cuda())
-    sparse = dw.o.float().clone()
-    dw.o.zero_()
+    torch.cuda.synchronize()
+    assert np.abs(dw.o.float().cpu().numpy() - want).max() <= 2e-2
+    dw.o.fill_(float("nan"))
     dw.dense_refresh()
-    assert (sparse - dw.o.float()).abs().max().item() <= 2e-2
+    torch.cuda.synchronize()
+    assert np.abs(dw.o.float().cpu().numpy() - want).max() <= 2e-2
 
 
 def test_select_then_attend_end_to_end_gpu_indices():
@@ -381,23 +391,40 @@ def test_batches_of_more_than_64_sequences():
     assert np.abs(got - oracle_attend(w, ref)[sparse_rows]).max() <= 2e-2
 
 
-def sample_rows(w, rows_per_seq, seed):
-    """Sub-workload with a few query rows of every sequence (all heads, full K/V): the oracle can
-    evaluate these one by one at full benchmark size."""
+def block_rows(w, seed):
+    """One query row out of every 32-row block of every sequence: every 32-query block of every wave of every
+    workgroup of a full-size launch gets one row checked."""
     rng = np.random.default_rng(seed)
     picks, qparts = [], []
     for b in range(w.batch):
         n = int(w.q_lens[b])
-        r = np.sort(rng.choice(n, size=min(n, rows_per_seq), replace=False)) + int(w.cu_q[b])
+        starts = np.arange(0, n, 32)
+        r = starts + rng.integers(0, np.minimum(32, n - starts)) + int(w.cu_q[b])
         picks.append(r)
         qparts.append(w.q[torch.from_numpy(r)])
-    sub = synth.Workload(w.name + "_sampled", w.dtype, w.n_q_heads, w.n_kv_heads, w.head_dim, torch.cat(qparts), w.k,
+    sub = synth.Workload(w.name + "_blockrows", w.dtype, w.n_q_heads, w.n_kv_heads, w.head_dim, torch.cat(qparts), w.k,
                          w.v, np.concatenate([[0], np.cumsum([len(p) for p in picks])]).astype(np.int32), w.cu_kv,
                          w.cu_k, w.seq_mode, w.softmax_scale)
     return sub, np.concatenate(picks)
 
 
-def test_dense_config4_full_size_sampled_rows():
+def check_whole_sequences(w, dw, seqs, idx):
+    """Every output element of the sequences `seqs` against the oracle."""
+    for b in seqs:
+        say(f"  whole sequence {b}: {int(w.q_lens[b])} query rows x {w.n_q_heads} heads over {int(w.kv_lens[b])} keys")
+        sub = synth.subset(w, [b])
+        sub_idx = None if idx is None else idx[:, int(w.cu_k[b]):int(w.cu_k[b + 1])]
+        if sub_idx is None:
+            sub_idx = np.zeros((w.n_q_heads, 0), np.int32)
+        want = oracle_attend(sub, np.ascontiguousarray(sub_idx))
+        got = dw.o[int(w.cu_q[b]):int(w.cu_q[b + 1])].float().cpu().numpy()
+        err = np.abs(got - want)
+        assert err.max() <= TOL[w.dtype], f"sequence {b}: max abs error {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+def test_dense_config4_full_size():
+    """Refresh workload at full size, in the launch the benchmark times: two whole sequences element by
+    element, and one row of every 32-query block of all of them."""
     w = synth.config(4)
     dw = hcsa.DeviceWorkload(w)
     say("dense config 4 full size")
@@ -405,13 +432,16 @@ def test_dense_config4_full_size_sampled_rows():
     dw.dense_refresh()
     torch.cuda.synchronize()
     assert torch.isfinite(dw.o.float()).all()
-    sub, rows = sample_rows(w, 6, 44)
+    check_whole_sequences(w, dw, [0, w.batch - 1], None)
+    sub, rows = block_rows(w, 44)
     ref = oracle_attend(sub, np.zeros((w.n_q_heads, 0), np.int32))
     got = dw.o[torch.from_numpy(rows).cuda()].float().cpu().numpy()
     assert np.abs(got - ref).max() <= 2e-2
 
 
 def test_mixed_config5_full_size():
+    """Mixed burst at full size through one attend call: every query row of every Reuse sequence, one whole
+    Refresh sequence, and one row of every 32-query block of the other Refresh sequences."""
     w = synth.config(5)
     dw, ref = check_select(w)
     say("attend config 5 full size (mixed, one call)")
@@ -419,10 +449,31 @@ def test_mixed_config5_full_size():
     dw.attend()
     torch.cuda.synchronize()
     assert torch.isfinite(dw.o.float()).all()
-    sub, rows = sample_rows(w, 4, 55)
+    sparse = [b for b in range(w.batch) if w.seq_mode[b] == 0]
+    dense = [b for b in range(w.batch) if w.seq_mode[b] == 1]
+    check_whole_sequences(w, dw, sparse + dense[:1], ref)
+    sub, rows = block_rows(w, 55)
     want = oracle_attend(sub, ref)
     got = dw.o[torch.from_numpy(rows).cuda()].float().cpu().numpy()
     assert np.abs(got - want).max() <= 2e-2
+
+
+@pytest.mark.parametrize("c", [3, 5])
+def test_paper_defaults_full_size(c):
+    """The paper's default setting (Table 2: retention 0.5, pooling kernel 3) on the batched Reuse workload
+    and on the mixed burst at full size: selection bit for bit, attention over the kept rows element by
+    element (Reuse rows), the Refresh sequences on one row per 32-query block."""
+    w = synth.at_retention(synth.config(c), 0.5)
+    dw, ref = check_select(w, pool_w=3, name=f"c{c} at retention 0.5, pool_w=3")
+    dw.o.fill_(float("nan"))
+    dw.attend()
+    torch.cuda.synchronize()
+    check_whole_sequences(w, dw, [b for b in range(w.batch) if w.seq_mode[b] == 0], ref)
+    if (w.seq_mode == 1).any():
+        sub, rows = block_rows(w, 66)
+        want = oracle_attend(sub, ref)
+        got = dw.o[torch.from_numpy(rows).cuda()].float().cpu().numpy()
+        assert np.abs(got - want).max() <= 2e-2
 
 
 # ------------------------------------------------------------------ packing (Section 4.5) and the packed Reuse step
@@ -518,6 +569,28 @@ def test_sequences_without_queries():
         dw, ref = check_select(w)
         assert np.array_equal(ref[:, :40], np.tile(np.arange(40), (4, 1)))
         check_attend(w, ref, dw=dw)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_attend_without_cu_k_zeroes_every_sequence_not_flagged_dense(dtype):
+    """cu_k = NULL (allowed with total_k = 0): nothing is kept anywhere, so a sequence not flagged dense gets
+    zeros (an empty kept set) and the flagged ones full attention; without modes every row is zero."""
+    w = custom(23, dtype, 8, 2, 128, [150, 90, 64], [32, 17, 64], [0, 0, 0], mode=np.array([1, 0, 1], np.uint8))
+    dw = hcsa.DeviceWorkload(w)
+    say(f"attend with cu_k = NULL, modes {w.seq_mode.tolist()} dtype={dtype}")
+    dw.o.fill_(float("nan"))
+    hcsa.dllm_hcsa_attend(dw.batch, None, None, 0, 0, dw.seq_mode, dw.o)
+    torch.cuda.synchronize()
+    ref = oracle.attend(synth.to_bits(w.q), synth.to_bits(w.k), synth.to_bits(w.v), w.cu_q, w.cu_kv, None, None, w.seq_mode,
+                        w.softmax_scale)
+    got = dw.o.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= TOL[dtype]
+    assert not got[32:49].any() and np.abs(got[:32]).max() > 0
+    dw.o.fill_(float("nan"))
+    hcsa.dllm_hcsa_attend(dw.batch, None, None, 0, 0, None, dw.o)
+    torch.cuda.synchronize()
+    assert not dw.o.float().cpu().numpy().any()
 
 
 # ------------------------------------------------------------------ HIP graph capture

@@ -461,6 +461,15 @@ def test_forced_tail_is_plain_selection_on_the_context_plus_the_block(pool_w):
             assert np.all(np.diff(mine) > 0)
     with pytest.raises(ValueError):
         oracle.select_ex(Q, K, cq, ckv, cu([10, 3, 9]), pool_w, n, False)    # fewer kept rows than forced ones
+    # The pooling window stops at the last candidate: scores (5, 1, 2, 0 | 100, 0) with the last two positions
+    # forced pool (w = 3) to (5, 5, 2, 2), so the one ranked row is position 0 (tie with 1, lower wins); a window
+    # reaching into the block would see the 100 at position 3.  One-hot keys, unit query: scores are exact.
+    if pool_w == 3:
+        kk = np.zeros((6, 1, 8), np.float32)
+        kk[:, 0, 0] = [5.0, 1.0, 2.0, 0.0, 100.0, 0.0]
+        qq = np.zeros((1, 1, 8), np.float32)
+        qq[0, 0, 0] = 1.0
+        assert oracle.select_ex(qq, kk, cu([1]), cu([6]), cu([3]), 3, 2, False).tolist() == [[0, 4, 5]]
 
 
 @pytest.mark.parametrize("pool_w", [1, 3])
@@ -479,6 +488,17 @@ def test_head_summed_selection_against_brute_force(pool_w):
         want = brute_topk(tot, keep[b])
         for h in range(4):
             assert np.array_equal(got[h, ck[b]:ck[b + 1]], want)
+    # The head sum is an fp32 chain in ascending head order from +0: with per-head scores (1e8, 1, -1e8, 1)
+    # at position 0 that chain gives ((0 + 1e8) + 1) - 1e8 + 1 = 1 (the first 1 is absorbed), the descending
+    # chain gives 0, and position 1 (scores 0.5, 0, 0, 0) wins or loses accordingly.  One-hot keys and a unit
+    # query make the per-head scores exactly these numbers.
+    c = np.zeros((2, 4, 8), np.float32)
+    c[0, :, 0] = [1e8, 1.0, -1e8, 1.0]
+    c[1, 0, 0] = 0.5
+    q1 = np.zeros((1, 4, 8), np.float32)
+    q1[0, :, 0] = 1.0
+    assert np.array_equal(oracle.select_ex(q1, c, cu([1]), cu([2]), cu([1]), pool_w=1, forced_tail=0, head_sum=True),
+                          np.zeros((4, 1), np.int32))
     # one head: summing changes nothing
     Q1, K1 = Q[:, :1].copy(), K[:, :1].copy()
     assert np.array_equal(oracle.select_ex(Q1, K1, cq, ckv, ck, pool_w, 0, True), oracle.select(Q1, K1, cq, ckv, ck, pool_w))
