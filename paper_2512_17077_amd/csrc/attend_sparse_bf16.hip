@@ -429,7 +429,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void attend_sparse_bf16_kernel(
 // the next go from global memory straight into a second pair of LDS buffers, and a wave's last round
 // already gathers its first tile of the next pass, so that those rows are in flight while the waves
 // merge.  LDS holds the eight waves' tiles, two query tiles and two sets of ids: 160 KB at D = 128.
-template <int D>
+// STREAM: the lists are the identity (idx = NULL: a packed cache, rows cu_k[b] .. cu_k[b+1]-1 of every head in
+// place).  No ids are fetched, staged or read back: a wave's tile is 32 consecutive rows from one base.
+template <int D, bool STREAM>
 __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ cu_q, const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ idx,
@@ -511,13 +513,13 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
   // (positions past the end repeat the last kept row, rows past the last query repeat the last query:
   // such rows are masked out of the softmax, such columns are never stored)
   auto prefetch = [&](const Pass& p, int bf) {
+    if constexpr (!STREAM) {
 #pragma unroll
-    for (int j = 0; j < kIds / 64; ++j) {
-      const int slot = j * 64 + lane;
-      const int t = min(p.c0 + (wave + (slot >> 5) * WAVES) * kTile + (slot & 31), p.c1 - 1);
-      if (idx != nullptr)
+      for (int j = 0; j < kIds / 64; ++j) {
+        const int slot = j * 64 + lane;
+        const int t = min(p.c0 + (wave + (slot >> 5) * WAVES) * kTile + (slot & 31), p.c1 - 1);
         load4_to_lds(p.rows + t, __builtin_amdgcn_readfirstlane(lds_addr(&sm_rows[bf][wave][j * 64])));
-      else sm_rows[bf][wave][slot] = t;   // NULL idx: identity lists (a packed cache)
+      }
     }
     if (kTile * CH >= WAVES * 64 || threadIdx.x < kTile * CH) {
       const int r = threadIdx.x / CH, c = (threadIdx.x % CH) ^ tile_swz<D>(r);
@@ -541,22 +543,39 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
   };
   // gather tile j of this wave in pass p
   auto fetch = [&](v4u (&kr)[NLD], v4u (&vr)[NLD], const Pass& p, int bf, int j) {
-    const int* my_rows = sm_rows[bf][wave];
+    if constexpr (STREAM) {
+      // rows c0 + (wave + j * WAVES) * 32 ..: positions past the end repeat the last row (masked in the softmax)
+      const int first = p.c0 + (wave + j * WAVES) * kTile;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const uint32_t off = __umul24(uint32_t(my_rows[j * kTile + (i * 64 + lane) / CH]), pitch) + coff;
-      kr[i] = load_once(p.kbase + off);
-      vr[i] = load_once(p.vbase + off);
+      for (int i = 0; i < NLD; ++i) {
+        const uint32_t off = __umul24(uint32_t(min(first + (i * 64 + lane) / CH, p.c1 - 1)), pitch) + coff;
+        kr[i] = load_once(p.kbase + off);
+        vr[i] = load_once(p.vbase + off);
+      }
+    } else {
+      const int* my_rows = sm_rows[bf][wave];
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const uint32_t off = __umul24(uint32_t(my_rows[j * kTile + (i * 64 + lane) / CH]), pitch) + coff;
+        kr[i] = load_once(p.kbase + off);
+        vr[i] = load_once(p.vbase + off);
+      }
     }
   };
 
   Pass cur, nxt;
   if (!next_pass(cur, false)) return;
   int bf = 0;
-  prefetch(cur, 0);
-  wait_tile_loads();
   v4u kra[NLD], vra[NLD];
-  if (wave < cur.ntiles) fetch(kra, vra, cur, 0, 0);
+  if constexpr (STREAM) {   // nothing to wait for before the first rows are asked for
+    if (wave < cur.ntiles) fetch(kra, vra, cur, 0, 0);
+    prefetch(cur, 0);
+    wait_tile_loads();
+  } else {
+    prefetch(cur, 0);
+    wait_tile_loads();
+    if (wave < cur.ntiles) fetch(kra, vra, cur, 0, 0);
+  }
   __syncthreads();   // the queries are in place
   for (;;) {
     nxt = cur;
@@ -736,12 +755,17 @@ hipError_t launch_attend_sparse_bf16(const Shape& s, const AttendPlan& p, const 
                      p.chunk_rows <= kMultiTilesPerWave * kWavesMulti * kTile &&
                      2 * int64_t(p.max_k) * s.batch >= 3 * int64_t(total_k);
   if (multi) {
-    if (s.d == 128)
-      attend_sparse_multi_bf16_kernel<128><<<n_cu, kWavesMulti * 64, 0, st>>>(
-          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s DLLM_CHECK_PASS);
-    else
-      attend_sparse_multi_bf16_kernel<64><<<n_cu, kWavesMulti * 64, 0, st>>>(
-          qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl, p.chunk_rows, p.n_chunks, n_cu, s DLLM_CHECK_PASS);
+    auto launch = [&](auto kernel) {
+      kernel<<<n_cu, kWavesMulti * 64, 0, st>>>(qh, kh, vh, cu_q, cu_kv, idx, cu_k, total_k, seq_mode, oh, po, pm, pl,
+                                                 p.chunk_rows, p.n_chunks, n_cu, s DLLM_CHECK_PASS);
+    };
+    if (idx == nullptr) {
+      if (s.d == 128) launch(attend_sparse_multi_bf16_kernel<128, true>);
+      else launch(attend_sparse_multi_bf16_kernel<64, true>);
+    } else {
+      if (s.d == 128) launch(attend_sparse_multi_bf16_kernel<128, false>);
+      else launch(attend_sparse_multi_bf16_kernel<64, false>);
+    }
   } else {
     dim3 grid(p.n_chunks, s.hq, s.batch);
     // the start order only matters when the workgroups cannot all be resident at once (two per compute unit)

@@ -27,8 +27,41 @@ def test_product_path_does_not_import_the_oracle():
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "hcsa_oracle" not in text, f
     bench = open(os.path.join(ROOT, "bench.py")).read()
-    assert bench.count("import oracle") == 1
-    assert bench.index("import oracle") > bench.index("def cpu_baseline") and bench.index("import oracle") < bench.index("def main")
+    lo, hi = bench.index("def cpu_baseline"), bench.index("def gqa_union_bytes")
+    assert lo < hi < bench.index("def main")
+    at = [i for i in range(len(bench)) if bench.startswith("import oracle", i)]
+    assert at and all(lo < i < hi for i in at)       # the baseline leg and the child process it starts, nowhere else
+
+
+def test_traffic_file_and_summary_agree_and_cover_the_roofline_kernels():
+    """bench.py takes roofline.traffic from profiles/hbm_traffic.json; the summary beside it (the table the
+    reader sees) must state the same figures, and every kernel a roofline names must be in the file."""
+    sys.path.insert(0, ROOT)
+    import bench
+    data = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
+    md = open(os.path.join(ROOT, "profiles", "hbm_traffic_pmc.md")).read()
+    rows = [[c.strip() for c in line.split("|")[1:-1]] for line in md.splitlines() if line.startswith("| ") and "---" not in line][1:]
+    seen = set()
+    for call, kernel, fetch, write, read_mb, write_mb, _ in rows:
+        name = kernel[:kernel.rindex("(")].strip()
+        t = data["calls"][call][name]
+        assert abs(float(fetch) - t["fetch_kib"]) <= 0.5 and abs(float(write) - t["write_kib"]) <= 0.5
+        assert abs(float(read_mb) - t["read_bytes"] / 1e6) <= 0.05 and abs(float(write_mb) - t["write_bytes"] / 1e6) <= 0.05
+        # the scaling: KiB x 1024 x (known probe bytes / probe counter)
+        assert abs(t["read_bytes"] - t["fetch_kib"] * 1024 * data["factor"]["FETCH_SIZE"]) <= 1024
+        seen.add((call, name))
+    assert len(seen) == sum(len(v) for v in data["calls"].values())
+    traffic = bench.load_traffic()
+    assert traffic == data["calls"]
+    for call, kernel in (("dense_refresh", "attend_dense_bf16_kernel"), ("attend_reuse", "attend_sparse_multi_bf16_kernel"),
+                         ("select_reuse", "score_kernel"), ("select_mixed", "score_kernel")):
+        total = bench.traffic_of(traffic, call, kernel)
+        assert total is not None and total > 0
+    # the figures are measured traffic of these workloads: within a few percent of the algorithmic bytes
+    from paper_2512_17077_amd import synth
+    w3 = synth.config(3)
+    assert 0.95 < bench.traffic_of(traffic, "attend_reuse", "attend_sparse_multi") / w3.attend_sparse_bytes() < 1.05
+    assert 0.95 < bench.traffic_of(traffic, "select_reuse", "score_kernel") / w3.select_bytes() < 1.05
 
 
 @pytest.mark.gpu
@@ -49,3 +82,11 @@ def test_bench_prints_one_json_line_with_the_contract_keys():
         assert key in roof, key
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-12
     assert 0.0 < out["roofline_reuse"]["frac"] < 1.0 and 0.0 < out["roofline_select"]["frac"] < 1.0
+    assert roof["traffic"] is not None and out["roofline_reuse"]["traffic"] is not None
+    assert set(out["small_config_call_us"]) == {"select_c1", "attend_c1", "select_c2", "attend_c2"}
+    assert all(v > 0 for v in out["reuse_select_options_gbps"].values())
+    assert out["call_ms_mean_min_median_warm"] is not None and len(out["call_ms_mean_min_median"]["attend_reuse"]) == 3
+    mixed = out["mixed_attend"]
+    assert mixed["reuse_part_bytes_gqa_union"] < mixed["reuse_part_bytes_per_head"]
+    assert mixed["refresh_part_read_bytes_counter"] is not None
+    assert out["config"]["step"] == ["select_reuse", "attend_reuse", "dense_refresh", "select_mixed", "attend_mixed"]

@@ -8,7 +8,7 @@ import pytest
 import torch
 
 import oracle
-from paper_2512_17077_amd import hcsa, synth
+from paper_2512_17077_amd import hcsa, synth, workload
 
 pytestmark = pytest.mark.gpu
 SENTINEL = -12345
@@ -29,7 +29,7 @@ def checked():
     hcsa.use_checked_library(False)
 
 
-def workload():
+def small_batch():
     return synth.make_workload("checked", synth.SEED_BASE + 4242, torch.bfloat16, 8, 2, 128, [300, 100], [32, 32], [50, 30])
 
 
@@ -41,8 +41,8 @@ def test_release_library_reports_no_checks():
 
 
 def test_valid_calls_match_the_oracle_and_leave_the_word_clear(checked):
-    w = workload()
-    dw = hcsa.DeviceWorkload(w)
+    w = small_batch()
+    dw = workload.DeviceWorkload(w)
     say("checked library: select, attend, pack, packed attend, dense on a valid batch")
     dw.select()
     ref = oracle.select(synth.to_bits(w.q), synth.to_bits(w.k), w.cu_q, w.cu_kv, w.cu_k)
@@ -66,8 +66,8 @@ def device_i32(x):
 
 
 def test_violations_are_reported_and_nothing_is_written(checked):
-    w = workload()
-    dw = hcsa.DeviceWorkload(w)
+    w = small_batch()
+    dw = workload.DeviceWorkload(w)
     Hq = w.n_q_heads
     good_idx = torch.from_numpy(oracle.select(synth.to_bits(w.q), synth.to_bits(w.k), w.cu_q, w.cu_kv, w.cu_k)).cuda()
 

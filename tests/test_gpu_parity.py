@@ -8,7 +8,7 @@ import pytest
 import torch
 
 import oracle
-from paper_2512_17077_amd import hcsa, synth
+from paper_2512_17077_amd import hcsa, synth, workload
 
 pytestmark = pytest.mark.gpu
 
@@ -31,7 +31,7 @@ def oracle_attend(w, idx):
 def check_select(w, pool_w=1, name=""):
     say(f"select {name or w.name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} "
         f"D={w.head_dim} maxL={int(w.kv_lens.max())} pool_w={pool_w}")
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     dw.idx.fill_(-7)
     dw.select(pool_w)
     torch.cuda.synchronize()
@@ -48,7 +48,7 @@ def check_select(w, pool_w=1, name=""):
 def check_attend(w, idx, name="", dw=None):
     say(f"attend {name or w.name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} "
         f"D={w.head_dim} maxk={int(w.keep.max())} maxq={int(w.q_lens.max())}")
-    dw = dw or hcsa.DeviceWorkload(w)
+    dw = dw or workload.DeviceWorkload(w)
     dw.o.fill_(float("nan"))
     dw.attend(torch.from_numpy(np.ascontiguousarray(idx)).to(dw.device))
     torch.cuda.synchronize()
@@ -217,7 +217,7 @@ def test_attend_ragged_keep_and_query_counts(dtype, D):
     idx = oracle_select(w)
     check_attend(w, idx)
     # k == 1 returns that V row exactly (bf16 in, bf16 out: no rounding at all)
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     dw.attend(torch.from_numpy(idx).cuda())
     row = int(idx[0, 0])
     assert torch.equal(dw.o[0, 0].cpu(), w.v[row, 0])
@@ -233,7 +233,7 @@ def test_attend_unsorted_and_repeated_indices():
 def test_attend_chunked_long_keep_lists():
     """Few (sequence, head) pairs with long kept lists are split over workgroups and merged."""
     w = custom(9, torch.bfloat16, 2, 1, 128, [4096, 700], [32, 32], [3000, 100], salient=0.05)
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     assert hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k) > 0
     check_attend(w, oracle_select(w), dw=dw)
     w2 = custom(10, torch.bfloat16, 2, 2, 64, [2048], [45], [2048])
@@ -251,7 +251,7 @@ def test_attend_more_lists_than_compute_units(D):
     check_attend(w, oracle_select(w))
     # long lists cut into chunks: 3 sequences x 32 heads x 3 chunks
     w2 = custom(13, torch.bfloat16, 32, 32, D, [5000, 2500, 100], [32, 9, 32], [4500, 2100, 7])
-    dw = hcsa.DeviceWorkload(w2)
+    dw = workload.DeviceWorkload(w2)
     assert hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k) > 0
     check_attend(w2, oracle_select(w2), dw=dw)
     # more than 64 sequences (walked in batch order)
@@ -272,7 +272,7 @@ def test_attend_keep_all_equals_dense_entry_point():
     dense_w = synth.with_keep(w, [0, 0])
     dense_w.seq_mode[:] = 1
     want = oracle_attend(dense_w, np.zeros((4, 0), np.int32))
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     dw.o.fill_(float("nan"))
     dw.attend(torch.from_numpy(idx).cuda())
     torch.cuda.synchronize()
@@ -298,7 +298,7 @@ def test_dense_small_and_ragged():
     w = custom(12, torch.bfloat16, 4, 2, 128, [100, 129, 64, 1, 300], [100, 5, 64, 3, 257], [0] * 5,
                mode=np.ones(5, np.uint8))
     check_attend(w, np.zeros((4, 0), np.int32), name="dense via attend")
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     dw.o.fill_(float("nan"))
     dw.dense_refresh()
     err = np.abs(dw.o.float().cpu().numpy() - oracle_attend(w, np.zeros((4, 0), np.int32))).max()
@@ -426,7 +426,7 @@ def test_dense_config4_full_size():
     """Refresh workload at full size, in the launch the benchmark times: two whole sequences element by
     element, and one row of every 32-query block of all of them."""
     w = synth.config(4)
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     say("dense config 4 full size")
     dw.o.fill_(float("nan"))
     dw.dense_refresh()
@@ -482,7 +482,7 @@ def check_pack_and_packed_attend(w, name):
     say(f"pack {name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
         f"maxk={int(w.keep.max())}")
     idx = oracle_select(w)
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     dw.idx.copy_(torch.from_numpy(idx))
     dw.pack()
     dw.k_packed.fill_(0)
@@ -521,7 +521,7 @@ def test_pack_and_packed_attend_config3_full():
 def check_select_ex(w, pool_w, forced_tail, head_sum, name):
     say(f"select_ex {name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
         f"maxL={int(w.kv_lens.max())} pool_w={pool_w} forced_tail={forced_tail} head_sum={head_sum}")
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     dw.idx.fill_(-7)
     dw.select_ex(pool_w, forced_tail, head_sum)
     torch.cuda.synchronize()
@@ -576,7 +576,7 @@ def test_attend_without_cu_k_zeroes_every_sequence_not_flagged_dense(dtype):
     """cu_k = NULL (allowed with total_k = 0): nothing is kept anywhere, so a sequence not flagged dense gets
     zeros (an empty kept set) and the flagged ones full attention; without modes every row is zero."""
     w = custom(23, dtype, 8, 2, 128, [150, 90, 64], [32, 17, 64], [0, 0, 0], mode=np.array([1, 0, 1], np.uint8))
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     say(f"attend with cu_k = NULL, modes {w.seq_mode.tolist()} dtype={dtype}")
     dw.o.fill_(float("nan"))
     hcsa.dllm_hcsa_attend(dw.batch, None, None, 0, 0, dw.seq_mode, dw.o)
@@ -603,7 +603,7 @@ def test_select_and_attend_replayed_from_a_hip_graph(which_workload):
     inputs then in the buffers (and the oracle's indices).  The ragged batch has more lists than
     compute units and takes the multi-list attend kernel."""
     w = synth.config(2) if which_workload.startswith("layer") else synth.config(3, scale_down=4)
-    dw = hcsa.DeviceWorkload(w)
+    dw = workload.DeviceWorkload(w)
     wss = torch.empty(max(256, hcsa.dllm_hcsa_select_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
     wsa = torch.empty(max(256, hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
     q_a = dw.q.clone()
