@@ -157,13 +157,13 @@ def cpu_baseline(w3, w4, w5):
     one_thread_c2 = """
 import sys, time
 sys.path.insert(0, {root!r})
-import ctypes, oracle
+import ctypes, oracle, torch
 from paper_2512_17077_amd import synth
-oracle.num_threads()                                   # loads the oracle (and with it the OpenMP runtime)
-ctypes.CDLL("libgomp.so.1").omp_set_num_threads(1)     # the environment variable may be pinned by the host
 w = synth.config(2)
 q, k, v = synth.to_bits(w.q), synth.to_bits(w.k), synth.to_bits(w.v)
-oracle.select(q, k, w.cu_q, w.cu_kv, w.cu_k)
+oracle.select(q, k, w.cu_q, w.cu_kv, w.cu_k)           # loads the oracle (and with it the OpenMP runtime)
+torch.set_num_threads(1)                               # torch sets the runtime's team size when it is first used
+ctypes.CDLL("libgomp.so.1").omp_set_num_threads(1)
 t0 = time.perf_counter()
 for _ in range(3):
     idx = oracle.select(q, k, w.cu_q, w.cu_kv, w.cu_k)
@@ -269,7 +269,7 @@ def main():
 
     REUSE = ("select_reuse", "attend_reuse", "pack_reuse", "attend_packed_reuse", "attend_shared_list_reuse",
              "select_pool3_reuse", "select_forced32_reuse", "select_headsum_reuse")
-    REFRESH = ("dense_refresh",)
+    REFRESH = ("dense_refresh", "dense_refresh_zero_inputs")
     MIXED = ("select_mixed", "attend_mixed", "attend_mixed_reuse_part_alone", "attend_mixed_refresh_part_alone")
     SMALL = ("select_c1", "attend_c1", "select_c2", "attend_c2")
     reuse, refresh, mixed = wanted("reuse", REUSE), wanted("refresh", REFRESH), wanted("mixed", MIXED)
@@ -314,6 +314,13 @@ def main():
                        for d, out in zip(d3, scratch_idx)])
     if refresh:
         add("dense_refresh", [lambda d=d: d.dense_refresh() for d in d4])
+        if not only_calls or "dense_refresh_zero_inputs" in only_calls:
+            # the same launches on all-zero Q, K, V: the same instructions and bytes, fewer bits toggling; the board's
+            # power limit sets the clock of this kernel, so the difference is what the data costs
+            d4z = [workload.DeviceWorkload(w4, "cuda:0") for _ in range(2)]
+            for d in d4z:
+                d.q.zero_(), d.k.zero_(), d.v.zero_()
+            add("dense_refresh_zero_inputs", [lambda d=d: d.dense_refresh() for d in d4z])
     union_bytes = None
     if mixed:
         ws5s = ws(hcsa.dllm_hcsa_select_workspace(d5[0].batch, d5[0].max_k))
@@ -344,7 +351,7 @@ def main():
                 d.select(workspace=wss)
             add(f"select_{tag}", [lambda d=d, wss=wss: d.select(workspace=wss) for d in ds])
             add(f"attend_{tag}", [lambda d=d, wsa=wsa: d.attend(workspace=wsa) for d in ds])
-    names = REUSE[:5] + REFRESH + MIXED + REUSE[5:] + SMALL
+    names = REUSE[:5] + REFRESH[:1] + MIXED + REUSE[5:] + REFRESH[1:] + SMALL
     order = [calls[n] for n in names if n in calls and (not only_calls or n in only_calls)]
     # what BASELINE's metric counts as the step: the whole hot path on the three workloads
     step_calls = ("select_reuse", "attend_reuse", "dense_refresh", "select_mixed", "attend_mixed")
@@ -460,6 +467,7 @@ def main():
         "reuse_select_gbps": select_gbps,
         "reuse_select_pct_of_hbm_peak": None if select_gbps is None else 100.0 * select_gbps / HBM_PEAK_GBPS,
         "refresh_tflops": refresh_tflops,
+        "refresh_tflops_zero_inputs": rate_tflops(w4.attend_dense_flops(), "dense_refresh_zero_inputs"),
         "refresh_pct_of_mfma_peak": None if refresh_tflops is None else 100.0 * refresh_tflops / MFMA_BF16_PEAK_TFLOPS,
         "mixed_select_gbps": mixed_sel_gbps,
         "mixed_select_pct_of_hbm_peak": None if mixed_sel_gbps is None else 100.0 * mixed_sel_gbps / HBM_PEAK_GBPS,
