@@ -117,8 +117,9 @@ dllm_status dllm_hcsa_select(const dllm_batch *batch,
  *     and values next to the cache.  With the block stored as the last n positions of every
  *     sequence, those n positions are always kept and never ranked: the k_b - n best of positions
  *     0 .. L_b-n-1 are chosen as above (the pooling window is clipped to these candidates) and the n
- *     block positions close the ascending list.  Requires n <= k_b for every sequence with k_b > 0
- *     (not checked on the device); n <= max_k is checked.
+ *     block positions close the ascending list.  Requires n <= k_b <= L_b for every sequence with k_b > 0;
+ *     n <= max_k is checked on the host, and a sequence that breaks the rest gets no list at all (its
+ *     part of idx_out is left as it was; the checked build also reports DLLM_CHECK_FORCED).
  * head_sum = 1          The shared selection of Section 2.4 Eq. 5: the pooled scores are summed over
  *     the query heads (fp32, ascending head, starting from +0), one TopK is taken per sequence under
  *     the same order, and every head's row of idx_out receives that list.

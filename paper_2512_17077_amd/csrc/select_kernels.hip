@@ -300,6 +300,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   const int kv0 = cu_kv[b];
   const int L = cu_kv[b + 1] - kv0 - forced_tail;   // candidates: the positions before the forced ones
   const int kb = kb_all - forced_tail;              // kept among the candidates
+  if (kb < 0 || L < kb) return;   // a precondition of the call is broken (fewer kept rows than forced ones, or more
+                                  // than there are candidates): write nothing rather than outside this list
   const int h_first = head_sum ? 0 : h, h_last = head_sum ? n_heads : h + 1;   // heads that receive this list
   uint32_t* keys = dyn;
 
@@ -485,6 +487,7 @@ __global__ __launch_bounds__(T) void topk_reg_kernel(
   const int kv0 = cu_kv[b];
   const int L = cu_kv[b + 1] - kv0 - forced_tail;
   const int kb = kb_all - forced_tail;
+  if (kb < 0 || L < kb) return;   // broken precondition (see topk_kernel): write nothing
   const int h_first = head_sum ? 0 : h, h_last = head_sum ? n_heads : h + 1;
   for (int t = tid; t < forced_tail; t += T)
     for (int hh = h_first; hh < h_last; ++hh) idx_out[int64_t(hh) * total_k + o0 + kb + t] = L + t;

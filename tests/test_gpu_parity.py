@@ -559,6 +559,22 @@ def test_select_ex_config3_head_summed():
     check_select_ex(synth.config(3), 1, 0, True, "c3 shared list")
 
 
+def test_forced_block_larger_than_a_kept_list_writes_nothing_for_that_sequence():
+    """forced_tail <= k_b cannot be checked on the host.  A sequence that breaks it gets no list (its part of
+    idx_out keeps what was there) instead of a write in front of its list; the others are selected as usual."""
+    w = custom(29, torch.bfloat16, 8, 2, 128, [300, 100, 200], [32, 32, 32], [50, 30, 64])
+    dw = workload.DeviceWorkload(w)
+    say("select_ex with forced_tail 40 on kept counts 50, 30, 64")
+    dw.idx.fill_(-7)
+    dw.select_ex(forced_tail=40)
+    torch.cuda.synchronize()
+    got = dw.idx.cpu().numpy()
+    assert (got[:, 50:80] == -7).all()
+    ok = synth.subset(w, [0, 2])
+    ref = oracle.select_ex(synth.to_bits(ok.q), synth.to_bits(ok.k), ok.cu_q, ok.cu_kv, ok.cu_k, 1, 40, False)
+    assert np.array_equal(got[:, :50], ref[:, :50]) and np.array_equal(got[:, 80:], ref[:, 50:])
+
+
 def test_sequences_without_queries():
     """A sequence may have no query rows this step (it only holds cache): selection then ranks a zero
     block sum (all ties, lowest positions win), attention has nothing to write for it, and its
