@@ -52,7 +52,8 @@ typedef __attribute__((ext_vector_type(16))) int i32x16;
 //   v[160:175], v[176:191]   pb_a, pb_b   packed probabilities of two consecutive steps, [qb][u][4]
 //   v[192 : 192 + 4*NT)      kop   K operands of the next score chain, [t][4]
 //   v[80:95]                 addr  LDS byte addresses: K operand [t], then V^T operand [rd][db] from +8
-//   v70 .. v75               lsum[2], nmz[2] (= -m z per block), mx[2] (lane maxima of the newest scores)
+//   a[.. + 16*2)             ls    row-sum blocks [qb][16] (only row 0 is used)
+//   v72 .. v75               nmz[2] (= -m z per block), mx[2] (lane maxima of the newest scores)
 //   v[76:79], v[224:255]     scratch of a step (logits in flight, V^T operand buffers)
 // C++ code may read and write the v-register variables between steps like any others, and may write q;
 // the accumulators are only ever handed from one assembly block to the next (this compiler cannot take
@@ -80,11 +81,25 @@ struct DenseTileLoad {
       "=v"(x[16 * (k) + 8]), "=v"(x[16 * (k) + 9]), "=v"(x[16 * (k) + 10]), "=v"(x[16 * (k) + 11]),               \
       "=v"(x[16 * (k) + 12]), "=v"(x[16 * (k) + 13]), "=v"(x[16 * (k) + 14]), "=v"(x[16 * (k) + 15])
 
+// Row sums are taken on the matrix cores: one more accumulator block per query block (ls) takes P^T times
+// a matrix whose first row is ones (the operand `ones`: lanes 0 and 32 hold eight bf16 ones, the others
+// zeros), so row 0 of that block (register 0 of lanes 0..31) is the sum of the bf16 probabilities of the
+// lane's query -- the same values the P V product multiplies, added in fp32 like its terms.  The vector
+// form (unpack each packed pair with a shift and a mask, two adds) costs four vector instructions per pair
+// of scores, a third of the step's vector work; v_dot2c_f32_bf16 does it in one but runs on the matrix
+// pipe and holds back the MFMAs (+18 cycles per MFMA), and summing the unrounded values is off by up to
+// 2^-8 of a row that one key rules.  Measured: 2 % of the launch.
+#define DLLM_LS_OUT_128 "={a[192:207]}"(ls[0]), "={a[208:223]}"(ls[1])
+#define DLLM_LS_OUT_64 "={a[96:111]}"(ls[0]), "={a[112:127]}"(ls[1])
+#define DLLM_LS_TIED(a, b) a(ls[0]), b(ls[1])
+
 template <>
 struct DenseState<128> {
   static constexpr int kAcc = 128;   // accumulator registers
   f32x16 acc[8], q[4], st_a[2], st_b[2], kop[2], pb_a, pb_b;
-  float lsum[2], nmz[2], mx[2];   // v70, v71; v72, v73 (= -m z per block); v74, v75 (lane maxima of the newest scores)
+  f32x16 ls[2];   // row sums (a-registers behind the queries, see above)
+  v4u ones;
+  float nmz[2], mx[2];   // v72, v73 (= -m z per block); v74, v75 (lane maxima of the newest scores)
   i32x16 addr;
 #define DLLM_ACC_OUT                                                                                          \
   "={a[0:15]}"(acc[0]), "={a[16:31]}"(acc[1]), "={a[32:47]}"(acc[2]), "={a[48:63]}"(acc[3]),                  \
@@ -99,9 +114,9 @@ struct DenseState<128> {
     if constexpr (AB)
       asm volatile(DLLM_DENSE_STEP_128_AB
                    : DLLM_ACC_OUT, "={v[128:143]}"(st_b[0]), "={v[144:159]}"(st_b[1]), "={v[160:175]}"(pb_a),
-                     "={v[192:207]}"(kop[0]), "={v[208:223]}"(kop[1]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v[192:207]}"(kop[0]), "={v[208:223]}"(kop[1]), DLLM_LS_OUT_128, "={v74}"(mx[0]),
                      "={v75}"(mx[1]), [grow] "=s"(grow)
-                   : DLLM_ACC_TIED, "11"(kop[0]), "12"(kop[1]), "13"(lsum[0]), "14"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[96:111]}"(st_a[0]),
+                   : DLLM_ACC_TIED, "11"(kop[0]), "12"(kop[1]), DLLM_LS_TIED("13", "14"), [ones] "v"(ones), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[96:111]}"(st_a[0]),
                      "{v[112:127]}"(st_a[1]), "{v[176:191]}"(pb_b), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep),
                      [koff] "n"(KOFF), [voff0] "n"(VOFF0), [voff1] "n"(VOFF1), [kt] "s"(tl.k), [vt] "s"(tl.v),
                      [lo0] "v"(tl.off[0]), [lo1] "v"(tl.off[1]), [lo2] "v"(tl.off[2]), [lo3] "v"(tl.off[3]),
@@ -110,9 +125,9 @@ struct DenseState<128> {
     else
       asm volatile(DLLM_DENSE_STEP_128_BA
                    : DLLM_ACC_OUT, "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1]), "={v[176:191]}"(pb_b),
-                     "={v[192:207]}"(kop[0]), "={v[208:223]}"(kop[1]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v[192:207]}"(kop[0]), "={v[208:223]}"(kop[1]), DLLM_LS_OUT_128, "={v74}"(mx[0]),
                      "={v75}"(mx[1]), [grow] "=s"(grow)
-                   : DLLM_ACC_TIED, "11"(kop[0]), "12"(kop[1]), "13"(lsum[0]), "14"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[128:143]}"(st_b[0]),
+                   : DLLM_ACC_TIED, "11"(kop[0]), "12"(kop[1]), DLLM_LS_TIED("13", "14"), [ones] "v"(ones), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[128:143]}"(st_b[0]),
                      "{v[144:159]}"(st_b[1]), "{v[160:175]}"(pb_a), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep),
                      [koff] "n"(KOFF), [voff0] "n"(VOFF0), [voff1] "n"(VOFF1)
                    : "memory", DLLM_DENSE_SCRATCH);
@@ -123,13 +138,13 @@ struct DenseState<128> {
   __device__ __forceinline__ void tail(i32x16 ad) {
     if constexpr (A)
       asm volatile(DLLM_DENSE_TAIL_128_A
-                   : DLLM_ACC_OUT
-                   : DLLM_ACC_TIED, "{v[160:175]}"(pb_a), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 256)
+                   : DLLM_ACC_OUT, DLLM_LS_OUT_128
+                   : DLLM_ACC_TIED, DLLM_LS_TIED("8", "9"), [ones] "v"(ones), "{v[160:175]}"(pb_a), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 256)
                    : "memory", DLLM_DENSE_SCRATCH);
     else
       asm volatile(DLLM_DENSE_TAIL_128_B
-                   : DLLM_ACC_OUT
-                   : DLLM_ACC_TIED, "{v[176:191]}"(pb_b), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 256)
+                   : DLLM_ACC_OUT, DLLM_LS_OUT_128
+                   : DLLM_ACC_TIED, DLLM_LS_TIED("8", "9"), [ones] "v"(ones), "{v[176:191]}"(pb_b), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 256)
                    : "memory", DLLM_DENSE_SCRATCH);
   }
   // S^T(0) into st_a from the K operands in kop
@@ -138,11 +153,15 @@ struct DenseState<128> {
                  : "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1])
                  : "{v[192:207]}"(kop[0]), "{v[208:223]}"(kop[1]), DLLM_Q_IN);
   }
-  __device__ __forceinline__ void acc_clear() { asm volatile(DLLM_DENSE_ACC_INIT_128 : DLLM_ACC_OUT); }
+  __device__ __forceinline__ void row_sums(float& l0, float& l1) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\tv_accvgpr_read_b32 %0, a192\n\tv_accvgpr_read_b32 %1, a208"
+                 : "=v"(l0), "=v"(l1) : "{a[192:207]}"(ls[0]), "{a[208:223]}"(ls[1]));
+  }
+  __device__ __forceinline__ void acc_clear() { asm volatile(DLLM_DENSE_ACC_INIT_128 : DLLM_ACC_OUT, DLLM_LS_OUT_128); }
   // acc[qb] *= al[qb]; waits out the matrix pipe first (results may be read only 12 wait states after the
   // MFMA was issued, and nothing but software enforces it)
   __device__ __forceinline__ void acc_scale(float al0, float al1) {
-    asm volatile(DLLM_DENSE_ACC_SCALE_128 : DLLM_ACC_OUT : DLLM_ACC_TIED, [al0] "v"(al0), [al1] "v"(al1) : DLLM_DENSE_SCRATCH);
+    asm volatile(DLLM_DENSE_ACC_SCALE_128 : DLLM_ACC_OUT, DLLM_LS_OUT_128 : DLLM_ACC_TIED, DLLM_LS_TIED("8", "9"), [al0] "v"(al0), [al1] "v"(al1) : DLLM_DENSE_SCRATCH);
   }
   // all accumulators of block qb, head_dim block db, after the matrix pipe has drained
   __device__ __forceinline__ void acc_read(float (&x)[kAcc]) {
@@ -171,7 +190,9 @@ template <>
 struct DenseState<64> {
   static constexpr int kAcc = 64;
   f32x16 acc[4], q[2], st_a[2], st_b[2], kop[1], pb_a, pb_b;
-  float lsum[2], nmz[2], mx[2];   // v70, v71; v72, v73 (= -m z per block); v74, v75 (lane maxima of the newest scores)
+  f32x16 ls[2];   // row sums (a-registers behind the queries, see above)
+  v4u ones;
+  float nmz[2], mx[2];   // v72, v73 (= -m z per block); v74, v75 (lane maxima of the newest scores)
   i32x16 addr;
 #define DLLM_ACC_OUT "={a[0:15]}"(acc[0]), "={a[16:31]}"(acc[1]), "={a[32:47]}"(acc[2]), "={a[48:63]}"(acc[3])
 #define DLLM_ACC_TIED "0"(acc[0]), "1"(acc[1]), "2"(acc[2]), "3"(acc[3])
@@ -182,9 +203,9 @@ struct DenseState<64> {
     if constexpr (AB)
       asm volatile(DLLM_DENSE_STEP_64_AB
                    : DLLM_ACC_OUT, "={v[128:143]}"(st_b[0]), "={v[144:159]}"(st_b[1]), "={v[160:175]}"(pb_a),
-                     "={v[192:207]}"(kop[0]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v[192:207]}"(kop[0]), DLLM_LS_OUT_64, "={v74}"(mx[0]),
                      "={v75}"(mx[1]), [grow] "=s"(grow)
-                   : DLLM_ACC_TIED, "7"(kop[0]), "8"(lsum[0]), "9"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[96:111]}"(st_a[0]), "{v[112:127]}"(st_a[1]),
+                   : DLLM_ACC_TIED, "7"(kop[0]), DLLM_LS_TIED("8", "9"), [ones] "v"(ones), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[96:111]}"(st_a[0]), "{v[112:127]}"(st_a[1]),
                      "{v[176:191]}"(pb_b), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep), [koff] "n"(KOFF), [voff0] "n"(VOFF0),
                      [voff1] "n"(VOFF1), [kt] "s"(tl.k), [vt] "s"(tl.v), [lo0] "v"(tl.off[0]), [lo1] "v"(tl.off[1]),
                      [wl] "s"(tl.wave_lds), [lk] "n"(LK), [lv] "n"(LV)
@@ -192,9 +213,9 @@ struct DenseState<64> {
     else
       asm volatile(DLLM_DENSE_STEP_64_BA
                    : DLLM_ACC_OUT, "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1]), "={v[176:191]}"(pb_b),
-                     "={v[192:207]}"(kop[0]), "={v70}"(lsum[0]), "={v71}"(lsum[1]), "={v74}"(mx[0]),
+                     "={v[192:207]}"(kop[0]), DLLM_LS_OUT_64, "={v74}"(mx[0]),
                      "={v75}"(mx[1]), [grow] "=s"(grow)
-                   : DLLM_ACC_TIED, "7"(kop[0]), "8"(lsum[0]), "9"(lsum[1]), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[128:143]}"(st_b[0]), "{v[144:159]}"(st_b[1]),
+                   : DLLM_ACC_TIED, "7"(kop[0]), DLLM_LS_TIED("8", "9"), [ones] "v"(ones), "{v72}"(nmz[0]), "{v73}"(nmz[1]), DLLM_Q_IN, "{v[128:143]}"(st_b[0]), "{v[144:159]}"(st_b[1]),
                      "{v[160:175]}"(pb_a), "{v[80:95]}"(addr), [zs] "s"(zs), [lazy] "s"(kLazyStep), [koff] "n"(KOFF), [voff0] "n"(VOFF0),
                      [voff1] "n"(VOFF1)
                    : "memory", DLLM_DENSE_SCRATCH);
@@ -203,13 +224,13 @@ struct DenseState<64> {
   __device__ __forceinline__ void tail(i32x16 ad) {
     if constexpr (A)
       asm volatile(DLLM_DENSE_TAIL_64_A
-                   : DLLM_ACC_OUT
-                   : DLLM_ACC_TIED, "{v[160:175]}"(pb_a), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 128)
+                   : DLLM_ACC_OUT, DLLM_LS_OUT_64
+                   : DLLM_ACC_TIED, DLLM_LS_TIED("4", "5"), [ones] "v"(ones), "{v[160:175]}"(pb_a), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 128)
                    : "memory", DLLM_DENSE_SCRATCH);
     else
       asm volatile(DLLM_DENSE_TAIL_64_B
-                   : DLLM_ACC_OUT
-                   : DLLM_ACC_TIED, "{v[176:191]}"(pb_b), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 128)
+                   : DLLM_ACC_OUT, DLLM_LS_OUT_64
+                   : DLLM_ACC_TIED, DLLM_LS_TIED("4", "5"), [ones] "v"(ones), "{v[176:191]}"(pb_b), "{v[80:95]}"(ad), [voff0] "n"(0), [voff1] "n"(16 * 128)
                    : "memory", DLLM_DENSE_SCRATCH);
   }
   __device__ __forceinline__ void score0() {
@@ -217,9 +238,13 @@ struct DenseState<64> {
                  : "={v[96:111]}"(st_a[0]), "={v[112:127]}"(st_a[1])
                  : "{v[192:207]}"(kop[0]), DLLM_Q_IN);
   }
-  __device__ __forceinline__ void acc_clear() { asm volatile(DLLM_DENSE_ACC_INIT_64 : DLLM_ACC_OUT); }
+  __device__ __forceinline__ void row_sums(float& l0, float& l1) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\tv_accvgpr_read_b32 %0, a96\n\tv_accvgpr_read_b32 %1, a112"
+                 : "=v"(l0), "=v"(l1) : "{a[96:111]}"(ls[0]), "{a[112:127]}"(ls[1]));
+  }
+  __device__ __forceinline__ void acc_clear() { asm volatile(DLLM_DENSE_ACC_INIT_64 : DLLM_ACC_OUT, DLLM_LS_OUT_64); }
   __device__ __forceinline__ void acc_scale(float al0, float al1) {
-    asm volatile(DLLM_DENSE_ACC_SCALE_64 : DLLM_ACC_OUT : DLLM_ACC_TIED, [al0] "v"(al0), [al1] "v"(al1) : DLLM_DENSE_SCRATCH);
+    asm volatile(DLLM_DENSE_ACC_SCALE_64 : DLLM_ACC_OUT, DLLM_LS_OUT_64 : DLLM_ACC_TIED, DLLM_LS_TIED("4", "5"), [al0] "v"(al0), [al1] "v"(al1) : DLLM_DENSE_SCRATCH);
   }
   __device__ __forceinline__ void acc_read(float (&x)[kAcc]) {
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -432,14 +457,17 @@ __global__ __launch_bounds__(kDenseWaves * 64, 1) void attend_dense_bf16_kernel(
       w.q_set(qb, t, 3, __uint_as_float(x.w));
     }
   }
-  // per query (lane pair l, l ^ 32): the row sum, -m * z for the running maximum m of the raw scores
-  // (w.lsum, w.nmz), the factor the output accumulators still have to take, and the accumulators
+  // per query (lane pair l, l ^ 32): -m * z for the running maximum m of the raw scores (w.nmz), the factor
+  // the accumulators (outputs and row sums) still have to take, and the accumulators
   float palpha[NQB];
   bool pending = false;   // some palpha != 1 (uniform)
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     palpha[qb] = 1.0f;
-    w.lsum[qb] = 0.0f;
+  }
+  {
+    const uint32_t one2 = (lane & 31) == 0 ? 0x3f803f80u : 0u;
+    w.ones = v4u{one2, one2, one2, one2};
   }
   w.acc_clear();
 #pragma unroll
@@ -549,7 +577,6 @@ __global__ __launch_bounds__(kDenseWaves * 64, 1) void attend_dense_bf16_kernel(
         const float mz_old = -w.nmz[qb];
         const float mz_new = fmaxf(mz_old, max_across_halves(w.mx[qb]) * zscale);
         const float alpha = __builtin_amdgcn_exp2f(mz_old - mz_new);
-        w.lsum[qb] *= alpha;
         palpha[qb] = alpha;
         w.nmz[qb] = -mz_new;
       }
@@ -611,10 +638,12 @@ __global__ __launch_bounds__(kDenseWaves * 64, 1) void attend_dense_bf16_kernel(
   }
   return;   // the counts sit where outputs would go
 #endif
+  float lrow[NQB];
+  w.row_sums(lrow[0], lrow[1]);   // lanes 0..31: the query's sum; lanes 32..63: row 4 of the block, zero
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const int qi = qbase + (wave * NQB + qb) * 32 + col;
-    const float l = sum_across_halves(w.lsum[qb]);
+    const float l = sum_across_halves(lrow[qb]);
     if (qi < nq) {
       const float inv = 1.0f / l;
 #pragma unroll

@@ -15,8 +15,9 @@ Run `python3 gen_dense_step.py` in this folder after changing the schedule; the 
 One step (iteration j) at D = 128, NQB = 2 blocks of 32 queries per wave:
     slots  0..15   S^T(j+1) = K(j+1) Q^T         MFMA(t, qb), K operand t shared by the two blocks
     slots 16..31   O^T += V(j-1)^T P(j-1)^T      MFMA(u, db, qb), V^T operand (u, db) shared likewise
+    slots 32..35   l += ones P(j-1)^T             row sums of the same probabilities, MFMA(u, qb)
     all slots      P(j) = exp2(S(j) z - m z)      on the scores of the previous step: per pair of scores
-                                                   2 fma, 2 exp, 1 cvt_pk (-> bf16 x 2), 2 add (row sum)
+                                                   2 fma, 2 exp, 1 cvt_pk (-> bf16 x 2)
     slots 20..31   row maxima of S(j+1)           16 max / max3
     LDS            16 transposing reads (V^T operands, four slots ahead of their MFMAs),
                    8 ds_read_b128 (K operands of step j+2, after the S chain has consumed the old ones)
@@ -32,10 +33,6 @@ NO_VALU = "--no-valu" in sys.argv
 NO_DS = "--no-ds" in sys.argv
 NO_KREAD = "--no-kread" in sys.argv   # keep the waits, drop the reads themselves
 NO_VREAD = "--no-vread" in sys.argv
-ROWSUM = "unpack"
-for _a in sys.argv[1:]:
-    if _a.startswith("--rowsum="):
-        ROWSUM = _a[9:]
 NO_LOADS = "--no-loads" in sys.argv   # keep the barrier, drop the global_load_lds (LDS keeps what the prologue loaded)
 
 # ---- register map (v-registers; a-registers are numbered separately)
@@ -66,7 +63,9 @@ def gen_step(D, cur, nxt, pnew, pold, with_scores=True, with_softmax=True, with_
     ROWB = 2 * D
     n_s = NT * 2 if with_scores else 0     # score MFMAs
     n_pv = 2 * NDB * 2                     # P V MFMAs
-    nslots = n_s + n_pv
+    n_ls = 4                               # row-sum MFMAs
+    nslots = n_s + n_pv + n_ls
+    LS = QR + 4 * NT * 2                   # a: ls[qb][16] after the queries
 
     # ---- MFMAs per slot
     mfma = []
@@ -83,6 +82,11 @@ def gen_step(D, cur, nxt, pnew, pold, with_scores=True, with_softmax=True, with_
                 a = ACC + 16 * (NDB * qb + db)
                 mfma.append((f"v_mfma_f32_32x32x16_bf16 {ar(a, 16)}, {vr(VOP + 4 * (p % NBUF), 4)}, "
                              f"{vr(pold + 4 * (2 * qb + u), 4)}, {ar(a, 16)}", ("v", p) if qb == 0 else None))
+    # row sums: row 0 of ones * P^T, accumulated like the outputs (the a-register blocks after the queries)
+    for u in range(2):
+        for qb in range(2):
+            a = LS + 16 * qb
+            mfma.append((f"v_mfma_f32_32x32x16_bf16 {ar(a, 16)}, %[ones], {vr(pold + 4 * (2 * qb + u), 4)}, {ar(a, 16)}", None))
 
     # ---- LDS reads per slot: (text, tag)
     ds = [[] for _ in range(nslots)]
@@ -109,7 +113,7 @@ def gen_step(D, cur, nxt, pnew, pold, with_scores=True, with_softmax=True, with_
         ds[s0].append(vread(p, 0))
         ds[s0 + 1].append(vread(p, 1))
     if with_scores:
-        free = [s for s in range(n_s, nslots) if not ds[s]]
+        free = [s for s in range(n_s, n_s + n_pv) if not ds[s]]
         assert len(free) >= NT, (len(free), NT)
         for t in range(NT):
             ds[free[t]].append((f"ds_read_b128 {vr(KOP + 4 * t, 4)}, {vr(ADDR + t)} offset:%[koff]", ("k", t)))
@@ -120,25 +124,13 @@ def gen_step(D, cur, nxt, pnew, pold, with_scores=True, with_softmax=True, with_
         ops = []
         pairs = [(qb, u, jj) for qb in range(2) for u in range(2) for jj in range(4)]
 
-        # Row sums are taken over the probabilities as rounded to bf16, the values the matrix cores multiply
-        # with V: a row ruled by one key then gives exactly that key's V row (a sum over the unrounded values
-        # would be off by up to 2^-8 of it).  v_dot2c_f32_bf16 adds a packed pair in one instruction, but it
-        # runs on the matrix pipe and every one of them holds back the MFMAs (measured: +18 cycles per MFMA);
-        # unpacking the pair with a shift and a mask and two plain adds overlaps with the MFMAs like all other
-        # vector work.  (ROWSUM: "unpack" as described, "dot" and "raw" = unrounded values for timing contrasts.)
+        # Row sums: the four extra MFMAs above add up the probabilities as rounded to bf16, the values the
+        # matrix cores multiply with V, so the vector units only convert.
         def finish(i):
             qb, u, jj = pairs[i]
             t0 = TMP + 2 * (i % 2)
             w = pnew + 4 * (2 * qb + u) + jj
-            cvt = [f"v_cvt_pk_bf16_f32 {vr(w)}, {vr(t0)}, {vr(t0 + 1)}"]
-            if ROWSUM == "dot":
-                return cvt, [f"v_dot2c_f32_bf16_e32 {vr(SM + qb)}, 0x3f803f80, {vr(w)}"], []
-            if ROWSUM == "raw":
-                return (cvt, [f"v_add_f32_e32 {vr(SM + qb)}, {vr(t0)}, {vr(SM + qb)}"],
-                        [f"v_add_f32_e32 {vr(SM + qb)}, {vr(t0 + 1)}, {vr(SM + qb)}"])
-            return (cvt + [f"v_lshlrev_b32_e32 {vr(t0)}, 16, {vr(w)}", f"v_and_b32_e32 {vr(t0 + 1)}, 0xffff0000, {vr(w)}"],
-                    [f"v_add_f32_e32 {vr(SM + qb)}, {vr(t0)}, {vr(SM + qb)}"],
-                    [f"v_add_f32_e32 {vr(SM + qb)}, {vr(t0 + 1)}, {vr(SM + qb)}"])
+            return [f"v_cvt_pk_bf16_f32 {vr(w)}, {vr(t0)}, {vr(t0 + 1)}"], [], []
 
         for i, (qb, u, jj) in enumerate(pairs):
             t0 = TMP + 2 * (i % 2)
@@ -261,7 +253,10 @@ def gen_score0(D):
 
 
 def gen_acc_init(D):
-    return [f"v_accvgpr_write_b32 a{i}, 0" for i in range(16 * 2 * (D // 32))]
+    regs = list(range(16 * 2 * (D // 32)))
+    ls = 16 * 2 * (D // 32) + 4 * (D // 16) * 2
+    regs += list(range(ls, ls + 32))        # the row-sum blocks behind the queries
+    return [f"v_accvgpr_write_b32 a{i}, 0" for i in regs]
 
 
 def gen_acc_scale(D):
@@ -274,6 +269,10 @@ def gen_acc_scale(D):
             lines += [f"v_accvgpr_read_b32 {vr(TMP + c)}, a{r}" for c, r in enumerate(regs)]
             lines += [f"v_mul_f32_e32 {vr(TMP + c)}, %[al{qb}], {vr(TMP + c)}" for c in range(4)]
             lines += [f"v_accvgpr_write_b32 a{r}, {vr(TMP + c)}" for c, r in enumerate(regs)]
+    ls = 2 * n + 4 * (D // 16) * 2   # the row sums: only row 0 of each block is ever non-zero
+    for qb in range(2):
+        lines += [f"v_accvgpr_read_b32 {vr(TMP)}, a{ls + 16 * qb}", f"v_mul_f32_e32 {vr(TMP)}, %[al{qb}], {vr(TMP)}",
+                  f"v_accvgpr_write_b32 a{ls + 16 * qb}, {vr(TMP)}"]
     lines += ["s_nop 7"]
     return lines
 
@@ -286,7 +285,7 @@ def gen_acc_read(k):
 def main():
     out = ["// Generated by gen_dense_step.py -- do not edit by hand.  One 32-key step of the dense Refresh kernel as",
            "// inline-assembly text over a fixed register map; see the generator for the schedule and the map.",
-           "// Named operands: %[zs] (softmax_scale * log2 e, scalar), %[koff] (byte offset of the K rows fetched",
+           "// Named operands: %[ones] (four v-registers: the A operand whose first row is bf16 ones), %[zs] (softmax_scale * log2 e, scalar), %[koff] (byte offset of the K rows fetched",
            "// for step j+2), %[voff0], %[voff1] (byte offsets of the V rows of step j-1, keys 0..15 and 16..31),",
            "// %[grow] (out, scalar pair: lanes whose newest scores outgrew the running maximum by more than %[lazy]);",
            "// in the _AB text (the first step of a tile) also %[kt], %[vt] (scalar pairs: first K / V row of the tile",
