@@ -433,16 +433,15 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(
   uint32_t before = incl - packed;
   for (int w = 0; w < wave; ++w) before += wave_tot[w];
   uint32_t gt_before = before & 0xffffu, eq_before = before >> 16;
+  // (both counters advance by selects, not in branches: with an increment in either arm of a branch the
+  // compiler keeps the pair in scratch memory and indexes it, and a kernel that needs scratch starts its
+  // waves more slowly)
   auto emit = [&](int j, bool above) {
-    int slot = -1;
-    if (above) {
-      slot = int(gt_before + min(eq_before, need_eq));
-      ++gt_before;
-    } else {
-      if (eq_before < need_eq) slot = int(gt_before + eq_before);
-      ++eq_before;
-    }
-    if (slot >= 0)
+    const uint32_t slot = gt_before + (above ? min(eq_before, need_eq) : eq_before);
+    const bool keep = above || eq_before < need_eq;
+    gt_before += above ? 1u : 0u;
+    eq_before += above ? 0u : 1u;
+    if (keep)
       for (int hh = h_first; hh < h_last; ++hh) idx_out[int64_t(hh) * total_k + o0 + slot] = j;
   };
   if (masks) {
