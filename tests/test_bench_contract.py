@@ -33,6 +33,19 @@ def test_product_path_does_not_import_the_oracle():
     assert at and all(lo < i < hi for i in at)       # the baseline leg and the child process it starts, nowhere else
 
 
+def test_ceilings_program_compiles_for_gfx950(tmp_path):
+    """ceilings.py builds ceilings.hip on the GPU machine at run time; keep it compiling (no GPU needed for that)."""
+    import shutil
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not installed")
+    out = tmp_path / "ceilings.o"
+    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        "-Wno-inline-asm", "-c", os.path.join(ROOT, "ceilings.hip"), "-o", str(out)],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert out.stat().st_size > 0
+
+
 def test_traffic_file_and_summary_agree_and_cover_the_roofline_kernels():
     """bench.py takes roofline.traffic from profiles/hbm_traffic.json; the summary beside it (the table the
     reader sees) must state the same figures, and every kernel a roofline names must be in the file."""
