@@ -512,6 +512,17 @@ def test_pack_and_packed_attend_ragged(dtype, D, Hq, Hkv):
                                  f"ragged {dtype} D={D}")
 
 
+@pytest.mark.parametrize("D", [128, 64])
+def test_packed_attend_long_ragged_lists_over_many_heads(D):
+    """The index-free path of the multi-list kernel: more (sequence, head, chunk) items than compute units, lists
+    cut into chunks and merged, several query tiles, a list of seven rows and one of none."""
+    w = custom(31, torch.bfloat16, 32, 32, D, [5000, 2500, 100, 900], [32, 9, 70, 32], [4500, 2100, 7, 0])
+    check_pack_and_packed_attend(w, f"long ragged lists, D={D}")
+    w2 = custom(32, torch.bfloat16, 32, 8, D, [900, 40, 300, 65, 700, 129, 77, 512, 33, 260, 1000, 90],
+                [32, 1, 7, 33, 32, 32, 70, 32, 0, 32, 32, 5], [800, 1, 33, 65, 517, 0, 77, 11, 32, 129, 31, 90])
+    check_pack_and_packed_attend(w2, f"twelve ragged sequences, grouped queries, D={D}")
+
+
 def test_pack_and_packed_attend_config3_full():
     check_pack_and_packed_attend(synth.config(3), "c3 full size")
 
