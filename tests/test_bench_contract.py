@@ -46,6 +46,33 @@ def test_ceilings_program_compiles_for_gfx950(tmp_path):
     assert out.stat().st_size > 0
 
 
+def test_traffic_tool_reads_a_counter_run(tmp_path):
+    """bench_traffic.read_run on a hand-made counter file: the copy probe is found, only launches after it count,
+    and a kernel's figure is the mean of its last three launches."""
+    sys.path.insert(0, ROOT)
+    import bench_traffic
+    header = ("Correlation_Id,Dispatch_Id,Agent_Id,Queue_Id,Process_Id,Thread_Id,Grid_Size,Kernel_Id,Kernel_Name,Workgroup_Size,"
+              "LDS_Block_Size,Scratch_Size,VGPR_Count,Accum_VGPR_Count,SGPR_Count,Counter_Name,Counter_Value,Start_Timestamp,"
+              "End_Timestamp")
+    add = "void at::native::vectorized_elementwise_kernel<4, at::native::CUDAFunctorOnSelf_add<int>, std::array<char*, 2ul> >(int)"
+    ker = "void dllm::score_kernel<2, 128, 1>(char const*, char const*)"
+    rows = [(1, ker, 1024, 256, 999.0),            # set-up launch, before the probe: ignored
+            (2, add, 1 << 26, 256, 524288.0),
+            (3, ker, 1024, 256, 500.0),            # warm-up
+            (4, ker, 1024, 256, 100.0), (5, ker, 1024, 256, 110.0), (6, ker, 1024, 256, 120.0),
+            (7, "void dllm::topk_reg_kernel<8, 512>(float const*)", 2048, 512, 7.0)]
+    d = tmp_path / "FETCH_SIZE" / "select_reuse"
+    d.mkdir(parents=True)
+    with open(d / "p_counter_collection.csv", "w") as f:
+        f.write(header + "\n")
+        for i, name, grid, wg, val in rows:
+            f.write(f'{i},{i},"Agent 1",1,1,1,{grid},1,"{name}",{wg},0,0,8,0,32,"FETCH_SIZE",{val},0,1\n')
+    probe, per = bench_traffic.read_run(str(d), "FETCH_SIZE")
+    assert probe == 524288.0
+    assert per["score_kernel<2, 128, 1>"] == ("4 x 256", 110.0)
+    assert per["topk_reg_kernel<8, 512>"] == ("4 x 512", 7.0)
+
+
 def test_traffic_file_and_summary_agree_and_cover_the_roofline_kernels():
     """bench.py takes roofline.traffic from profiles/hbm_traffic.json; the summary beside it (the table the
     reader sees) must state the same figures, and every kernel a roofline names must be in the file."""
