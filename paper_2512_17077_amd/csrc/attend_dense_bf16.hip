@@ -27,6 +27,7 @@
 //     old scale during iteration j+1, are rescaled one iteration later.
 //   - The loop is unrolled over one turn of the rings (eight steps), so every LDS address is a register
 //     fixed before the loop plus an immediate offset.
+#include <algorithm>
 #include <type_traits>
 #include <utility>
 
@@ -291,26 +292,82 @@ __global__ __launch_bounds__(kDenseWaves * 64, 1) void attend_dense_bf16_kernel(
 
   __shared__ __attribute__((aligned(16))) char smem[2 * kDenseRing * TILEB];   // K ring, V ring
 
-  // Workgroups are handed to the eight XCDs round-robin by launch order, and each XCD has its own
-  // L2.  Renumber so that the workgroups that stream the same K/V -- the query tiles of the query
-  // heads that share one KV head of one sequence -- land on one XCD (launch ids equal modulo 8)
-  // and share its L2, while consecutive (sequence, KV head) pairs go to different XCDs.
-  const int nx = gridDim.x, units = s.hkv * gridDim.z;
-  const int n = blockIdx.x + nx * (blockIdx.y + gridDim.y * blockIdx.z);
-  int qtile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if ((units & 7) == 0) {
-    const int per_unit = s.group * nx;
-    const int j = n >> 3;   // position in this XCD's own launch sequence
-    const int r = j % per_unit, unit = (j / per_unit) * 8 + (n & 7);
-    qtile = r % nx;
-    h = (unit % s.hkv) * s.group + r / nx;
-    b = unit / s.hkv;
+  // Which query tile of which (sequence, head) this workgroup takes.
+  //
+  // Batches of up to 64 sequences are launched as a one-dimensional grid with just enough workgroups for the
+  // query tiles the batch can have (the host bounds their number from total_q), and every workgroup finds
+  // its tile itself: lane i looks at sequence i, a prefix sum over the tiles of the sequences that are
+  // attended densely places the workgroup.  A mixed batch then starts no workgroups for its sparse
+  // sequences, and a ragged one none for the query tiles short sequences do not have (an empty workgroup
+  // holds a whole compute unit until it has found out that it is empty).  Larger batches use the
+  // three-dimensional grid (query tile, head, sequence) with an early exit.
+  //
+  // Workgroups are handed to the eight XCDs round-robin by launch order, and each XCD has its own L2.
+  // The numbering is such that the workgroups that stream the same K/V -- the query tiles of the query
+  // heads that share one KV head of one sequence -- land on one XCD (launch ids equal modulo 8) and
+  // share its L2, while consecutive (sequence, KV head) pairs go to different XCDs.
+  int qtile, h, b, q0, nq, kv0, L;
+  if (gridDim.y == 1 && gridDim.z == 1) {
+    const int lane0 = threadIdx.x & 63;
+    int my_q0 = 0, my_nq = 0, my_kv0 = 0, my_L = 0, my_tiles = 0;
+    if (lane0 < s.batch) {
+      my_q0 = cu_q[lane0];
+      my_nq = cu_q[lane0 + 1] - my_q0;
+      my_kv0 = cu_kv[lane0];
+      my_L = cu_kv[lane0 + 1] - my_kv0;
+      const bool dense = which == 2 || (seq_mode != nullptr && seq_mode[lane0] == DLLM_SEQ_DENSE);
+      my_tiles = dense ? (my_nq + kDenseRows - 1) / kDenseRows : 0;
+    }
+    const int incl = int(wave_inclusive_sum(uint32_t(my_tiles)));
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    const int n = blockIdx.x;
+    int place;   // position of the tile in (sequence, tile) order, times what follows
+    uint64_t m;
+    if ((s.hkv & 7) == 0) {
+      // XCD x = n % 8 takes KV heads x, x + 8, ...; within the XCD: sequence, KV head, query head of its group, tile
+      const int per_seq = s.group * (s.hkv >> 3);
+      place = n >> 3;
+      if (place >= total * per_seq) return;
+      m = __builtin_amdgcn_ballot_w64(incl * per_seq > place);
+      b = __builtin_ctzll(m);
+      const int tb = __builtin_amdgcn_readlane(my_tiles, b);
+      const int rem = place - (__builtin_amdgcn_readlane(incl, b) - tb) * per_seq;
+      const int per_head_group = tb * s.group;
+      const int kvh = (rem / per_head_group) * 8 + (n & 7), r = rem % per_head_group;
+      qtile = r % tb;
+      h = kvh * s.group + r / tb;
+    } else {
+      place = n / s.hq;
+      h = n % s.hq;
+      if (place >= total) return;
+      m = __builtin_amdgcn_ballot_w64(incl > place);
+      b = __builtin_ctzll(m);
+      qtile = place - (__builtin_amdgcn_readlane(incl, b) - __builtin_amdgcn_readlane(my_tiles, b));
+    }
+    q0 = __builtin_amdgcn_readlane(my_q0, b);
+    nq = __builtin_amdgcn_readlane(my_nq, b);
+    kv0 = __builtin_amdgcn_readlane(my_kv0, b);
+    L = __builtin_amdgcn_readlane(my_L, b);
+  } else {
+    const int nx = gridDim.x, units = s.hkv * gridDim.z;
+    const int n = blockIdx.x + nx * (blockIdx.y + gridDim.y * blockIdx.z);
+    qtile = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    if ((units & 7) == 0) {
+      const int per_unit = s.group * nx;
+      const int j = n >> 3;   // position in this XCD's own launch sequence
+      const int r = j % per_unit, unit = (j / per_unit) * 8 + (n & 7);
+      qtile = r % nx;
+      h = (unit % s.hkv) * s.group + r / nx;
+      b = unit / s.hkv;
+    }
+    if (which == 1 && !(seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE)) return;
+    q0 = cu_q[b];
+    nq = cu_q[b + 1] - q0;
+    kv0 = cu_kv[b];
+    L = cu_kv[b + 1] - kv0;
   }
-  if (which == 1 && !(seq_mode != nullptr && seq_mode[b] == DLLM_SEQ_DENSE)) return;
-  const int q0 = cu_q[b], nq = cu_q[b + 1] - q0;
   const int qbase = qtile * kDenseRows;
   if (qbase >= nq) return;
-  const int kv0 = cu_kv[b], L = cu_kv[b + 1] - kv0;
   const int g = h / s.group;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int col = lane & 31, hf = lane >> 5;
@@ -666,7 +723,13 @@ hipError_t launch_attend_dense_bf16(const Shape& s, const void* q, const void* k
                                     const int32_t* cu_q, const int32_t* cu_kv, const uint8_t* seq_mode, int which,
                                     void* o, hipStream_t st) {
   if (s.max_q == 0) return hipSuccess;   // no sequence has a query: nothing to write
-  dim3 grid((s.max_q + kDenseRows - 1) / kDenseRows, s.hq, s.batch);
+  const int64_t nx = (s.max_q + kDenseRows - 1) / kDenseRows;
+  dim3 grid(unsigned(nx), s.hq, s.batch);
+  if (s.batch <= 64) {
+    // the workgroups place themselves (see the kernel): as many as the batch can have query tiles, times the heads
+    const int64_t tiles = std::min<int64_t>(int64_t(s.total_q) / kDenseRows + s.batch, nx * s.batch);
+    if (tiles * s.hq < (int64_t(1) << 31)) grid = dim3(unsigned(tiles * s.hq), 1, 1);
+  }
   const uint16_t *qh = static_cast<const uint16_t*>(q), *kh = static_cast<const uint16_t*>(k),
                  *vh = static_cast<const uint16_t*>(v);
   if (s.d == 128)

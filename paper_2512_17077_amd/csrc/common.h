@@ -97,6 +97,23 @@ __device__ __forceinline__ v4u load_once(const void* p) {
   return *static_cast<const v4u*>(p);
 #endif
 }
+// Inclusive prefix sum over the 64 lanes of a wave (all lanes active) through the data-parallel
+// primitives: shifts by 1, 2, 4, 8 within each row of 16 lanes, then the last lane of row 0 (2) is
+// added to row 1 (3), then lane 31 to rows 2 and 3.  A lane without a source adds zero.
+template <int Ctrl, int RowMask>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t x) {
+  return x + uint32_t(__builtin_amdgcn_update_dpp(0, int(x), Ctrl, RowMask, 0xf, false));
+}
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x) {
+  x = dpp_add<0x111, 0xf>(x);   // row_shr:1
+  x = dpp_add<0x112, 0xf>(x);   // row_shr:2
+  x = dpp_add<0x114, 0xf>(x);   // row_shr:4
+  x = dpp_add<0x118, 0xf>(x);   // row_shr:8
+  x = dpp_add<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 

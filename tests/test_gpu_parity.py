@@ -391,6 +391,38 @@ def test_batches_of_more_than_64_sequences():
     assert np.abs(got - oracle_attend(w, ref)[sparse_rows]).max() <= 2e-2
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,n", [(16, 8, 64, 64), (32, 16, 128, 20), (6, 3, 128, 64), (8, 8, 128, 1)])
+def test_dense_tiles_place_themselves_on_ragged_and_mixed_batches(Hq, Hkv, D, n):
+    """Up to 64 sequences the dense kernel's workgroups find their own (sequence, head, query tile) from a prefix
+    sum over the densely attended sequences: ragged query counts around the 256-row tile, sequences without
+    queries, sparse sequences in between, KV-head counts that are and are not multiples of eight, through
+    both entry points."""
+    rng = np.random.default_rng(1000 + Hq + n)
+    lens = rng.integers(1, 700, size=n)
+    lens[rng.integers(0, n)] = 256
+    lens[rng.integers(0, n)] = 513
+    mode = (rng.random(n) < 0.5).astype(np.uint8)
+    mode[0] = 1
+    qlens = np.where(mode == 1, lens, np.minimum(lens, 32))
+    if n > 2:
+        qlens[1] = 0          # a sequence that only holds cache
+    keep = np.where(mode == 1, 0, np.maximum(1, lens // 3))
+    w = custom(40 + n, torch.bfloat16, Hq, Hkv, D, lens.tolist(), qlens.tolist(), keep.tolist(), mode=mode)
+    if (mode == 0).any():
+        dw, ref = check_select(w)
+        check_attend(w, ref, dw=dw)
+    # every sequence densely, queries = all its rows where it has any
+    wd = custom(41 + n, torch.bfloat16, Hq, Hkv, D, lens.tolist(), np.where(qlens > 0, lens, 0).tolist(), [0] * n,
+                mode=np.ones(n, np.uint8))
+    dd = workload.DeviceWorkload(wd)
+    dd.o.fill_(float("nan"))
+    dd.dense_refresh()
+    torch.cuda.synchronize()
+    got = dd.o.float().cpu().numpy().astype(np.float64)
+    want = oracle_attend(wd, np.zeros((Hq, 0), np.int32))
+    assert np.isfinite(got).all() and np.abs(got - want).max() <= TOL[wd.dtype]
+
+
 def block_rows(w, seed):
     """One query row out of every 32-row block of every sequence: every 32-query block of every wave of every
     workgroup of a full-size launch gets one row checked."""
