@@ -222,6 +222,8 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch* batch, const int32_t* cu_k, in
   return device_result(e, "dllm_hcsa_select");
 }
 
+int32_t dllm_hcsa_set_select_form(int32_t form) { return dllm::set_select_form(form); }
+
 dllm_status dllm_hcsa_select_static(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
                                     int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out,
                                     void* hip_stream) {

@@ -14,6 +14,7 @@
 // lane owns a whole row, each wave stages 64 rows through LDS: 16-byte chunks are loaded so that a
 // row's chunks sit in neighbouring lanes, written to LDS with an XOR swizzle, and read back one row
 // per lane without bank conflicts.
+#include <atomic>
 #include <type_traits>
 #include <utility>
 
@@ -599,6 +600,348 @@ __global__ __launch_bounds__(T) void topk_reg_kernel(
   }
 }
 
+// ------------------------------------------------------------------ scores and top-k in one workgroup
+// One workgroup per (sequence, KV head) walks the head's whole K column once, keeps the keys of its
+// GT query heads in registers (one key per lane, tile and head) and ranks them there: the scores never
+// travel to HBM and back and the lists need no second launch.  Lists of up to kFusedWaves * kFusedTiles
+// * 64 positions; the arithmetic, the tie rule and the output order are those of the kernels above.
+//
+// Ranking is a radix select over digits of 10, 11 and 11 bits.  The first histogram is counted while
+// the column streams in (its atomics hide under the memory waits); the other two count only the keys
+// that share the digits found so far, and the third is skipped for a head whose threshold bin holds
+// kept keys only.  Each head's histogram is scanned by one wave, in two levels (a lane sums a run of
+// bins, the owner's run is then looked at one bin per lane).  Compaction goes through a bitmap of the
+// kept positions (see there).
+constexpr int kFusedWaves = 8, kFusedTiles = 16;
+typedef __attribute__((ext_vector_type(16))) uint32_t u32x16;
+constexpr int kBinsA = 1024, kBinsB = 2048;   // digits: key >> 22, (key >> 11) & 2047, key & 2047
+
+template <int ES, int D, int GT>
+struct FusedLds {   // byte offsets inside the workgroup's dynamic LDS
+  static constexpr size_t stage = size_t(kFusedWaves) * 64 * D * ES;            // the waves' tiles while streaming
+  static constexpr size_t hist_bc = size_t(GT) * 2 * kBinsB * 4;                // afterwards: second and third histograms
+  static constexpr size_t kept = size_t(GT) * kFusedWaves * kFusedTiles * 64 * 4;   // at the end: the kept positions [GT][8192]
+  static constexpr size_t region0 = stage > hist_bc ? (stage > kept ? stage : kept) : (hist_bc > kept ? hist_bc : kept);
+  static constexpr size_t off_a = region0;                                      // first histogram [GT][kBinsA]
+  static constexpr size_t off_counts = off_a + size_t(GT) * kBinsA * 4;         // two bitmaps [GT][waves * tiles] of 64 bits, [2][waves] totals
+  static constexpr size_t off_res = off_counts + size_t(GT) * kFusedWaves * kFusedTiles * 16 + 2 * kFusedWaves * 4;   // [GT][4]
+  static constexpr size_t off_sums = off_res + size_t(GT) * 16;                 // [GT][D]
+  static constexpr size_t bytes = off_sums + size_t(GT) * D * 4;
+};
+
+// The bin that holds the kth-largest of the keys counted in hrow[0 .. NB) (bins descend from NB - 1), the
+// rank of that key inside the bin and the bin's count: {bin, rank, count}, the same in every lane.
+template <int NB>
+__device__ __forceinline__ uint3 pick_bin(const uint32_t* hrow, uint32_t kth, int lane) {
+  constexpr int BPL = NB / 64;   // bins per lane; lane 0 owns the highest
+  static_assert(BPL % 4 == 0 && BPL <= 64, "runs of whole 16-byte words, one bin per lane in the second level");
+  const uint32_t* run_lo = hrow + NB - BPL * (lane + 1);
+  uint32_t tot = 0;
+#pragma unroll
+  for (int i = 0; i < BPL / 4; ++i) {
+    const uint4 v = *reinterpret_cast<const uint4*>(run_lo + 4 * i);
+    tot += v.x + v.y + v.z + v.w;
+  }
+  const uint32_t incl = wave_inclusive_sum(tot);
+  const uint64_t m1 = __ballot(incl - tot < kth && kth <= incl);
+  const int owner = m1 ? __builtin_ctzll(m1) : 0;
+  const uint32_t above = uint32_t(__builtin_amdgcn_readlane(int(incl - tot), owner));
+  const int top = NB - BPL * owner - 1;   // the owner's highest bin
+  const uint32_t c = lane < BPL ? hrow[top - lane] : 0u;
+  const uint32_t incl2 = wave_inclusive_sum(c) + above;
+  const uint64_t m2 = __ballot(incl2 - c < kth && kth <= incl2);
+  const int j = m2 ? __builtin_ctzll(m2) : 0;
+  return make_uint3(uint32_t(top - j), kth - uint32_t(__builtin_amdgcn_readlane(int(incl2 - c), j)),
+                    uint32_t(__builtin_amdgcn_readlane(int(c), j)));
+}
+
+// v[lane u] = x (x the same in all lanes).  A select, not v_writelane_b32: x usually comes straight from
+// a vector compare, and a lane write that reads a compare's result in the next instruction was seen
+// to pick up the previous compare's.
+__device__ __forceinline__ void set_lane(uint32_t& v, uint32_t x, int u) { v = int(threadIdx.x & 63) == u ? x : v; }
+
+template <int ES, int D, int GT>
+__global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void select_fused_kernel(
+    const char* __restrict__ k, const char* __restrict__ q, const int32_t* __restrict__ cu_q,
+    const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k, int32_t total_k, int32_t forced_tail,
+    int32_t* __restrict__ idx_out, Shape s DLLM_CHECK_PARAM) {
+  DLLM_CHECK_EXIT();
+  constexpr int ROWB = D * ES, CH = ROWB / 16, EPC = 16 / ES, W = kFusedWaves, NT = kFusedTiles, T = W * 64;
+  static_assert(NT == 16 && W * NT == 128, "sixteen tiles per wave, two (wave, tile) counts per lane");
+  static_assert(GT <= W, "one wave scans one head's histogram");
+  using Lds = FusedLds<ES, D, GT>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  v4u* mine_all = reinterpret_cast<v4u*>(lds);
+  uint32_t* hist_b = reinterpret_cast<uint32_t*>(lds);            // [GT][kBinsB], once streaming is over
+  uint32_t* hist_c = hist_b + GT * kBinsB;                        // [GT][kBinsB]
+  uint32_t* hist_a = reinterpret_cast<uint32_t*>(lds + Lds::off_a);
+  uint32_t* res = reinterpret_cast<uint32_t*>(lds + Lds::off_res);
+  float* sums = reinterpret_cast<float*>(lds + Lds::off_sums);
+
+  const int b = blockIdx.x / s.hkv, g = (blockIdx.x + b) % s.hkv;   // (rotation: see score_kernel)
+  int ck0 = cu_k[b], ck1 = cu_k[b + 1], kv0 = cu_kv[b], kv1 = cu_kv[b + 1], q0 = cu_q[b], q1 = cu_q[b + 1];
+  asm volatile("" : "+s"(ck0), "+s"(ck1), "+s"(kv0), "+s"(kv1), "+s"(q0), "+s"(q1));
+  if (ck1 == ck0) return;
+  const int L = kv1 - kv0, Lc = L - forced_tail, kb = ck1 - ck0 - forced_tail;
+  if (kb < 0 || Lc < kb) return;   // broken precondition (see topk_kernel): write nothing
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int32_t* __restrict__ out = idx_out + int64_t(g * GT) * total_k + ck0;
+  for (int t = tid; t < forced_tail; t += T)
+#pragma unroll
+    for (int hh = 0; hh < GT; ++hh) out[int64_t(hh) * total_k + kb + t] = Lc + t;
+  if (kb <= 0) return;
+
+  const int nt = (Lc + 63) >> 6, tpw = (nt + W - 1) / W;   // tpw <= NT: the host checked the longest list
+  const int first = wave * tpw * 64;
+  const int ntiles = max(0, min(min(tpw, NT), nt - wave * tpw));
+  const char* base = k + (int64_t(kv0) * s.kv_tok + int64_t(g) * s.kv_head) * ES + (lane % CH) * 16;
+  const int64_t row_pitch = s.kv_tok * ES;
+  v4u* mine = mine_all + wave * 64 * CH;
+  const int sw = swz<CH>(lane);
+  v4u regs[CH];
+  auto fetch = [&](int r0) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int row = min(r0 + (i * 64 + lane) / CH, L - 1);
+      regs[i] = load_once(base + row * row_pitch);
+    }
+  };
+  if (ntiles > 0) fetch(first);
+
+  for (int t = tid; t < GT * kBinsA; t += T) hist_a[t] = 0;
+  {   // block sums of this KV head's query heads, ascending rows (as in score_kernel)
+    const int nq = q1 - q0;
+    const int64_t qpitch = s.q_tok * ES;
+    auto widen = [](const char* p) -> float {
+      if constexpr (ES == 2)
+        return __uint_as_float(uint32_t(*reinterpret_cast<const uint16_t*>(p)) << 16);
+      else
+        return *reinterpret_cast<const float*>(p);
+    };
+    for (int e = tid; e < GT * D; e += T) {
+      const char* p = q + (int64_t(q0) * s.q_tok + int64_t(g * GT + e / D) * s.q_head + e % D) * ES;
+      float a = 0.0f;
+      int i = 0;
+      for (; i + 32 <= nq; i += 32) {
+        float x[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) x[j] = widen(p + (i + j) * qpitch);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) a = a + x[j];
+      }
+      for (; i < nq; ++i) a = a + widen(p + i * qpitch);
+      sums[e] = a;
+    }
+    __syncthreads();
+  }
+  constexpr int NQ = D / 16;
+  float vq[GT][NQ];
+  {
+    const float* qs = sums + (lane & 15);
+#pragma unroll
+    for (int t = 0; t < GT; ++t)
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) vq[t][i] = qs[t * D + 16 * i];
+  }
+
+  // key of tile u for head t in k<t>[u]; 0, below every real key, where there is no position
+  // (four named vectors: an array of them is not kept in registers)
+  u32x16 k0 = u32x16(0u), k1 = k0, k2 = k0, k3 = k0;
+  for (int it = 0; it < ntiles; ++it) {
+    const int r0 = first + it * 64;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int f = i * 64 + lane, row = f / CH, c = f % CH;
+      mine[row * CH + (c ^ swz<CH>(row))] = regs[i];
+    }
+    if (it + 1 < ntiles) fetch(r0 + 64);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float acc[GT];
+#pragma unroll
+    for (int t = 0; t < GT; ++t) acc[t] = 0.0f;
+    auto chunk = [&](auto cc) {
+      constexpr int c = decltype(cc)::value;
+      const v4u x = mine[lane * CH + (c ^ sw)];
+      float kv[EPC];
+      if constexpr (ES == 2) {
+        kv[0] = bf16_lo(x.x); kv[1] = bf16_hi(x.x); kv[2] = bf16_lo(x.y); kv[3] = bf16_hi(x.y);
+        kv[4] = bf16_lo(x.z); kv[5] = bf16_hi(x.z); kv[6] = bf16_lo(x.w); kv[7] = bf16_hi(x.w);
+      } else {
+        kv[0] = __uint_as_float(x.x); kv[1] = __uint_as_float(x.y);
+        kv[2] = __uint_as_float(x.z); kv[3] = __uint_as_float(x.w);
+      }
+#pragma unroll
+      for (int t = 0; t < GT; ++t) acc[t] = fma_row_bcast<(c * EPC) % 16, EPC>(acc[t], vq[t][(c * EPC) / 16], kv);
+    };
+    for_each_index(chunk, std::make_integer_sequence<int, CH>{});
+    const bool valid = r0 + lane < Lc;
+    uint32_t key[GT];
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+      key[t] = valid ? order_key(acc[t] + 0.0f) : 0u;
+      if (valid) atomicAdd(&hist_a[t * kBinsA + (key[t] >> 22)], 1u);
+    }
+    k0[it] = key[0];
+    if constexpr (GT > 1) k1[it] = key[1];
+    if constexpr (GT > 2) { k2[it] = key[2]; k3[it] = key[3]; }
+    __builtin_amdgcn_wave_barrier();
+  }
+  __syncthreads();   // every wave is done with its staging tile: the space now holds the later histograms
+  {
+    uint4* z = reinterpret_cast<uint4*>(hist_b);
+    for (int t = tid; t < GT * 2 * kBinsB / 4; t += T) z[t] = make_uint4(0, 0, 0, 0);
+  }
+  uint32_t key[GT][NT];
+#pragma unroll
+  for (int u = 0; u < NT; ++u) {
+    key[0][u] = k0[u];
+    if constexpr (GT > 1) key[1][u] = k1[u];
+    if constexpr (GT > 2) { key[2][u] = k2[u]; key[3][u] = k3[u]; }
+  }
+
+  // wave w < GT scans the histogram of head w and leaves {bin, rank, count} for all
+  auto scan_and_share = [&](const uint32_t* h, auto nb, uint32_t kth) {
+    constexpr int NB = decltype(nb)::value;
+    if (wave < GT) {
+      const uint3 r = pick_bin<NB>(h + wave * NB, kth, lane);
+      if (lane == 0) { res[4 * wave] = r.x; res[4 * wave + 1] = r.y; res[4 * wave + 2] = r.z; }
+    }
+    __syncthreads();
+  };
+  // a value every lane read from the same LDS word, as a scalar
+  auto shared = [](uint32_t x) { return uint32_t(__builtin_amdgcn_readfirstlane(int(x))); };
+  const int my_head = wave % GT;
+  uint32_t prefix[GT], kk[GT], tot_eq[GT];
+  scan_and_share(hist_a, std::integral_constant<int, kBinsA>{}, uint32_t(kb));   // (its barrier also covers the clearing above)
+  uint32_t my_kk = res[4 * my_head + 1];   // kk[my_head], read by address: indexing the register array would go through memory
+#pragma unroll
+  for (int t = 0; t < GT; ++t) { prefix[t] = shared(res[4 * t]); kk[t] = shared(res[4 * t + 1]); }
+#pragma unroll
+  for (int t = 0; t < GT; ++t)
+#pragma unroll
+    for (int u = 0; u < NT; ++u)
+      if ((key[t][u] >> 22) == prefix[t]) atomicAdd(&hist_b[t * kBinsB + ((key[t][u] >> 11) & (kBinsB - 1))], 1u);
+  __syncthreads();
+  scan_and_share(hist_b, std::integral_constant<int, kBinsB>{}, my_kk);
+  // A head whose threshold bin holds nothing but kept keys is settled after 21 bits: every key from
+  // the bin's lowest value on is kept, whatever the last digit of the k-th largest is.  (Likely when the
+  // bins are as thinly filled as here, two thousand of them for the keys of one first-level bin.)
+  my_kk = res[4 * my_head + 1];
+  const bool my_settled = res[4 * my_head + 2] == my_kk && res[4 * my_head] != 0;
+  bool settled[GT], all_settled = true;
+#pragma unroll
+  for (int t = 0; t < GT; ++t) {
+    prefix[t] = (prefix[t] << 11) | shared(res[4 * t]);
+    kk[t] = shared(res[4 * t + 1]);
+    settled[t] = shared(res[4 * t + 2]) == kk[t] && prefix[t] != 0;
+    all_settled = all_settled && settled[t];
+  }
+  if (!all_settled) {   // (the same in every thread)
+#pragma unroll
+    for (int t = 0; t < GT; ++t)
+      if (!settled[t]) {
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+          if ((key[t][u] >> 11) == prefix[t]) atomicAdd(&hist_c[t * kBinsB + (key[t][u] & (kBinsB - 1))], 1u);
+      }
+    __syncthreads();
+    if (wave < GT && !my_settled) {
+      const uint3 r = pick_bin<kBinsB>(hist_c + wave * kBinsB, my_kk, lane);
+      if (lane == 0) { res[4 * wave] = r.x; res[4 * wave + 1] = r.y; res[4 * wave + 2] = r.z; }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int t = 0; t < GT; ++t) {
+    if (settled[t]) {
+      prefix[t] = prefix[t] << 11;   // the lowest key of the bin: all keys from here on are kept
+      kk[t] = tot_eq[t] = 1;         // (read below as "every key equal to the threshold is kept")
+    } else {
+      prefix[t] = (prefix[t] << 11) | shared(res[4 * t]);   // key of the k-th largest
+      kk[t] = shared(res[4 * t + 1]);                       // how many keys equal to it are kept (lowest positions first)
+      tot_eq[t] = shared(res[4 * t + 2]);
+    }
+  }
+
+  // Compaction.  A ballot over a tile is the tile's 64 bits of the head's keep-bitmap, so each wave
+  // leaves one word per tile in LDS.  Then the workgroup is dealt out anew, one thread per word (two
+  // waves per head): a prefix sum over the words' population counts gives every word its first slot,
+  // the thread walks the set bits of its word and writes their positions into LDS, and the finished
+  // lists go out in whole lines.  Keys equal to the threshold have a bitmap of their own, used only
+  // when not all of them are kept (scores that tie exactly): a word then keeps its first few equal
+  // keys, as many as the rule "lower position first" leaves for it.
+  static_assert(T == 4 * 128 && GT <= 4, "one thread per tile of each of up to four heads");
+  constexpr int kWords = W * NT;   // tiles, and so bitmap words, per head
+  uint64_t* bitmap = reinterpret_cast<uint64_t*>(lds + Lds::off_counts);   // [GT][kWords] keys above the threshold
+  uint64_t* bitmap_eq = bitmap + GT * kWords;                              // [GT][kWords] keys equal to it
+  uint32_t* wave_tot = reinterpret_cast<uint32_t*>(bitmap_eq + GT * kWords);   // [2][W]
+  constexpr int kKeptPerHead = W * NT * 64;
+  int32_t* kept = reinterpret_cast<int32_t*>(lds);   // [GT][kKeptPerHead], in the histograms' space
+  bool ties = false;
+#pragma unroll
+  for (int t = 0; t < GT; ++t) {
+    const bool all_eq = kk[t] == tot_eq[t];
+    const uint32_t thr = all_eq ? prefix[t] - 1 : prefix[t];   // (a threshold key is never 0)
+    ties = ties || !all_eq;
+    uint32_t mlo = 0, mhi = 0;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      const uint64_t bg = __ballot(key[t][u] > thr);
+      set_lane(mlo, uint32_t(bg), u);
+      set_lane(mhi, uint32_t(bg >> 32), u);
+    }
+    if (lane < ntiles) bitmap[t * kWords + wave * tpw + lane] = uint64_t(mlo) | (uint64_t(mhi) << 32);
+    if (!all_eq) {
+      uint32_t elo = 0, ehi = 0;
+#pragma unroll
+      for (int u = 0; u < NT; ++u) {
+        const uint64_t be = __ballot(key[t][u] == thr);
+        set_lane(elo, uint32_t(be), u);
+        set_lane(ehi, uint32_t(be >> 32), u);
+      }
+      if (lane < ntiles) bitmap_eq[t * kWords + wave * tpw + lane] = uint64_t(elo) | (uint64_t(ehi) << 32);
+      if (tid == 0) res[4 * t + 3] = kk[t];
+    } else if (tid == 0) {
+      res[4 * t + 3] = 0;
+    }
+  }
+  __syncthreads();
+  const int th = wave >> 1, word = tid & 127;   // this thread's head and tile from here on
+  const bool live = th < GT && word < nt;
+  // exclusive prefix of x over the 128 threads of a head (two waves), through wave_tot[which]
+  auto head_prefix = [&](uint32_t x, int which) {
+    const uint32_t incl = wave_inclusive_sum(x);
+    if (lane == 63) wave_tot[which * W + wave] = incl;
+    __syncthreads();
+    return incl - x + ((wave & 1) ? wave_tot[which * W + wave - 1] : 0u);
+  };
+  uint64_t m = live ? bitmap[th * kWords + word] : 0ull;
+  if (ties) {   // (the same in every thread)
+    const uint32_t need_eq = live ? res[4 * th + 3] : 0u;
+    uint64_t e = (live && need_eq != 0) ? bitmap_eq[th * kWords + word] : 0ull;
+    const uint32_t ce = uint32_t(__builtin_popcountll(e));
+    const uint32_t eq_before = head_prefix(ce, 1);
+    const uint32_t allowed = need_eq > eq_before ? min(ce, need_eq - eq_before) : 0u;
+    for (uint32_t c = ce; c > allowed; --c) e &= ~(1ull << (63 - __builtin_clzll(e)));   // drop the highest
+    m |= e;
+  }
+  uint32_t slot = head_prefix(uint32_t(__builtin_popcountll(m)), 0);
+  {
+    int32_t* __restrict__ o = kept + th * kKeptPerHead;
+    const int p0 = word * 64;
+    uint32_t half = uint32_t(m);
+    for (; half != 0; half &= half - 1) o[slot++] = p0 + __builtin_ctz(half);
+    half = uint32_t(m >> 32);
+    for (; half != 0; half &= half - 1) o[slot++] = p0 + 32 + __builtin_ctz(half);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < GT; ++t)
+    for (int i = tid; i < kb; i += T) out[int64_t(t) * total_k + i] = kept[t * kKeptPerHead + i];
+}
+
 // ------------------------------------------------------------------ host side
 SelectPlan plan_select(const Shape& s) {
   SelectPlan p;
@@ -635,11 +978,75 @@ static hipError_t launch_score(const Shape& s, const void* k, const void* q, con
   return launch(score_kernel<ES, D, 1>);
 }
 
+static std::atomic<int32_t> g_select_form{DLLM_SELECT_FORM_AUTO};
+int32_t set_select_form(int32_t form) {
+  if (form != DLLM_SELECT_FORM_AUTO && form != DLLM_SELECT_FORM_TWO_LAUNCHES && form != DLLM_SELECT_FORM_ONE_LAUNCH)
+    return -1;
+  return g_select_form.exchange(form);
+}
+
+// Shapes select_fused_kernel can take.
+static bool fused_can(const Shape& s, dllm_dtype dt, int32_t pool_w, int32_t head_sum) {
+  if (pool_w != 1 || head_sum) return false;
+  if (s.group != 1 && s.group != 2 && s.group != 4) return false;
+  if (s.d * (dt == DLLM_BF16 ? 2 : 4) > 256) return false;
+  return s.max_kv <= kFusedWaves * kFusedTiles * 64;
+}
+// ... and where it pays (measured on batches of equal lists, 1 to 4 query heads per KV head, lists of
+// 2048 to 8192): each (sequence, KV head) pair is one workgroup that takes most of a compute unit's
+// LDS, so the pairs run in rounds of one per compute unit.  The form wins by 5 to 30 % when the last
+// round is mostly full, three quarters of the compute units in a single round, four fifths when there
+// are several, and loses up to 2x when a few pairs leave most of the chip idle.  Lists of very
+// different lengths make the rounds uneven (measured: 2 % slower on 16 sequences of 770 to 3411
+// positions), so the batch must also be fairly even: mean length at least 3/4 of the longest.
+static int compute_units() {
+  static std::atomic<int> cached{0};
+  int n = cached.load();
+  if (n > 0) return n;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    n = 256;
+  cached.store(n);
+  return n;
+}
+static bool fused_pays(const Shape& s) {
+  const int64_t pairs = int64_t(s.batch) * s.hkv, cus = compute_units();
+  const int64_t rounds = (pairs + cus - 1) / cus;
+  const bool full = rounds == 1 ? 4 * pairs >= 3 * cus : 5 * pairs >= 4 * rounds * cus;
+  const bool even = 4 * int64_t(s.total_kv) >= 3 * int64_t(s.batch) * s.max_kv;
+  return full && even;
+}
+
+template <int ES, int D>
+static hipError_t launch_fused(const Shape& s, const void* k, const void* q, const int32_t* cu_q,
+                               const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t forced_tail,
+                               int32_t* idx_out, hipStream_t st) {
+  const char *kp = static_cast<const char*>(k), *qp = static_cast<const char*>(q);
+  auto launch = [&](auto kernel, size_t lds) -> hipError_t {
+    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
+    if (ea != hipSuccess) return ea;
+    kernel<<<dim3(s.batch * s.hkv), dim3(kFusedWaves * 64), lds, st>>>(kp, qp, cu_q, cu_kv, cu_k, total_k, forced_tail,
+                                                                      idx_out, s DLLM_CHECK_PASS);
+    return hipGetLastError();
+  };
+  if (s.group == 4) return launch(select_fused_kernel<ES, D, 4>, FusedLds<ES, D, 4>::bytes);
+  if (s.group == 2) return launch(select_fused_kernel<ES, D, 2>, FusedLds<ES, D, 2>::bytes);
+  return launch(select_fused_kernel<ES, D, 1>, FusedLds<ES, D, 1>::bytes);
+}
+
 hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,
                          const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t max_k,
                          int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out, void* ws,
                          hipStream_t st) {
   (void)max_k;
+  const int32_t form = g_select_form.load();
+  if (form != DLLM_SELECT_FORM_TWO_LAUNCHES && fused_can(s, dt, pool_w, head_sum) &&
+      (form == DLLM_SELECT_FORM_ONE_LAUNCH || fused_pays(s)))
+    return dt == DLLM_BF16 ? (s.d == 128 ? launch_fused<2, 128>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, idx_out, st)
+                                         : launch_fused<2, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, idx_out, st))
+                           : launch_fused<4, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, idx_out, st);
   const SelectPlan p = plan_select(s);
   float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_scores);
   hipError_t e;

@@ -24,9 +24,11 @@ DLLM_ERR_WORKSPACE = -3
 DLLM_ERR_DEVICE = -4
 DLLM_F32, DLLM_BF16 = 0, 1
 DLLM_SEQ_SPARSE, DLLM_SEQ_DENSE = 0, 1
+DLLM_SELECT_FORM_AUTO, DLLM_SELECT_FORM_TWO_LAUNCHES, DLLM_SELECT_FORM_ONE_LAUNCH = 0, 1, 2
 
 EXPORTS = [
     "dllm_hcsa_select_workspace", "dllm_hcsa_select", "dllm_hcsa_select_ex", "dllm_hcsa_select_static",
+    "dllm_hcsa_set_select_form",
     "dllm_hcsa_attend_workspace", "dllm_hcsa_attend",
     "dllm_dense_refresh_attend_workspace", "dllm_dense_refresh_attend",
     "dllm_hcsa_pack", "dllm_hcsa_precondition_errors",
@@ -85,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.dllm_hcsa_select.argtypes = [P, vp, i32, i32, i32, vp, vp, sz, vp]
         L.dllm_hcsa_select_ex.restype = ctypes.c_int
         L.dllm_hcsa_select_ex.argtypes = [P, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.dllm_hcsa_set_select_form.restype = i32
+        L.dllm_hcsa_set_select_form.argtypes = [i32]
         L.dllm_hcsa_select_static.restype = ctypes.c_int
         L.dllm_hcsa_select_static.argtypes = [P, vp, i32, i32, i32, i32, i32, vp, vp]
         L.dllm_hcsa_attend_workspace.restype = sz
@@ -198,6 +202,14 @@ def dllm_hcsa_select_ex(batch: DllmBatch, cu_k: torch.Tensor, total_k: int, max_
 
 
 DLLM_SELECT_STATIC_BYTES = 32 << 20
+
+
+def dllm_hcsa_set_select_form(form: int) -> int:
+    """Process-wide choice between the two forms of selection (DLLM_SELECT_FORM_*); returns the previous one."""
+    prev = int(lib().dllm_hcsa_set_select_form(int(form)))
+    if prev < 0:
+        raise ValueError(f"select form {form} is none of DLLM_SELECT_FORM_AUTO/TWO_LAUNCHES/ONE_LAUNCH")
+    return prev
 
 
 def dllm_hcsa_select_static(batch: DllmBatch, cu_k: torch.Tensor, total_k: int, max_k: int, idx_out: torch.Tensor,

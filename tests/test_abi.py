@@ -27,6 +27,20 @@ def test_library_exports_every_declared_symbol():
     assert hcsa.last_error() == "" or isinstance(hcsa.last_error(), str)
 
 
+def test_select_form_setter_returns_the_previous_form_and_rejects_unknown_values():
+    L = hcsa.lib()
+    first = L.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_ONE_LAUNCH)
+    try:
+        assert first in (hcsa.DLLM_SELECT_FORM_AUTO, hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES, hcsa.DLLM_SELECT_FORM_ONE_LAUNCH)
+        assert L.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES) == hcsa.DLLM_SELECT_FORM_ONE_LAUNCH
+        assert L.dllm_hcsa_set_select_form(7) == -1 and L.dllm_hcsa_set_select_form(-1) == -1
+        assert L.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_AUTO) == hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES   # unchanged by the rejects
+        with pytest.raises(ValueError):
+            hcsa.dllm_hcsa_set_select_form(3)
+    finally:
+        L.dllm_hcsa_set_select_form(first)
+
+
 def good_batch():
     b = hcsa.DllmBatch()
     b.dtype = hcsa.DLLM_BF16

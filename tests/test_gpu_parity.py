@@ -28,20 +28,35 @@ def oracle_attend(w, idx):
                          w.seq_mode, w.softmax_scale)
 
 
+SELECT_FORMS = [(hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES, "two launches"), (hcsa.DLLM_SELECT_FORM_ONE_LAUNCH, "one launch"),
+                (hcsa.DLLM_SELECT_FORM_AUTO, "the library's choice")]
+
+
+def run_select_in_every_form(dw, ref, call):
+    """Selection has two forms with identical results; every parity case goes through both (the one-launch form
+    wherever it takes the shape) and through the library's own choice, each against the oracle."""
+    try:
+        for form, label in SELECT_FORMS:
+            hcsa.dllm_hcsa_set_select_form(form)
+            dw.idx.fill_(-7)
+            call()
+            torch.cuda.synchronize()
+            got = dw.idx.cpu().numpy()
+            if not np.array_equal(got, ref):
+                bad = np.argwhere(got != ref)
+                h, t = bad[0]
+                raise AssertionError(f"{label}: {len(bad)} of {ref.size} indices differ; first at head {h}, slot {t}: "
+                                     f"gpu {got[h, t]} oracle {ref[h, t]}")
+    finally:
+        hcsa.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_AUTO)
+
+
 def check_select(w, pool_w=1, name=""):
     say(f"select {name or w.name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} "
         f"D={w.head_dim} maxL={int(w.kv_lens.max())} pool_w={pool_w}")
     dw = workload.DeviceWorkload(w)
-    dw.idx.fill_(-7)
-    dw.select(pool_w)
-    torch.cuda.synchronize()
-    got = dw.idx.cpu().numpy()
     ref = oracle_select(w, pool_w)
-    if not np.array_equal(got, ref):
-        bad = np.argwhere(got != ref)
-        h, t = bad[0]
-        raise AssertionError(f"{len(bad)} of {ref.size} indices differ; first at head {h}, slot {t}: "
-                             f"gpu {got[h, t]} oracle {ref[h, t]}")
+    run_select_in_every_form(dw, ref, lambda: dw.select(pool_w))
     return dw, ref
 
 
@@ -122,6 +137,30 @@ def test_select_list_lengths_around_4096(pool_w):
     check_select(w, pool_w=pool_w)
     w2 = custom(7, torch.bfloat16, 4, 2, 64, [4097, 4096, 8192], [32, 32, 32], [4097, 1000, 4000])
     check_select(w2, pool_w=pool_w)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D", [(torch.bfloat16, 16, 4, 128), (torch.bfloat16, 8, 4, 64), (torch.float32, 4, 4, 64)])
+def test_select_in_one_launch_edges(dtype, Hq, Hkv, D):
+    """The shapes the one-launch form is built around: lists that end inside, at and just past a 64-row tile and
+    a wave's run of tiles, the longest list it takes (8192), kept counts of 1 and of everything, scores that tie
+    exactly across many tiles (equal keys are kept from the lowest position up, so a tile keeps only its share),
+    a forced block, and more (sequence, KV head) pairs than one round of workgroups."""
+    lens = [8192, 8191, 4160, 1025, 1024, 513, 512, 511, 129, 64, 63, 2, 1]
+    keep = [8192, 1, 2080, 1000, 256, 513, 100, 510, 128, 1, 63, 1, 1]
+    w = custom(41, dtype, Hq, Hkv, D, lens, [32] * len(lens), keep, salient=0.02)
+    check_select(w, name="edges")
+    # exact ties: every sequence repeats its first 40 rows many times over, so each score value occurs in up to
+    # eight tiles and the threshold value is shared by rows of which only the first few are kept
+    off = 0
+    for L in lens:
+        for r in range(40, L, 40):
+            n = min(40, L - r)
+            w.k[off + r:off + r + n] = w.k[off:off + n].clone()
+        off += L
+    check_select(w, name="edges, rows repeated every 40 positions")
+    check_select_ex(w, 1, 1, False, "edges, forced block of 1 on repeated rows")
+    many = custom(42, dtype, Hq, 4 * Hkv if Hq % (4 * Hkv) == 0 else Hkv, D, [700] * 80, [32] * 80, [70] * 80)
+    check_select(many, name="more pairs than compute units")
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,D", [(torch.bfloat16, 32, 8, 128), (torch.bfloat16, 16, 16, 64),
@@ -565,16 +604,8 @@ def check_select_ex(w, pool_w, forced_tail, head_sum, name):
     say(f"select_ex {name} dtype={w.dtype} B={w.batch} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
         f"maxL={int(w.kv_lens.max())} pool_w={pool_w} forced_tail={forced_tail} head_sum={head_sum}")
     dw = workload.DeviceWorkload(w)
-    dw.idx.fill_(-7)
-    dw.select_ex(pool_w, forced_tail, head_sum)
-    torch.cuda.synchronize()
-    got = dw.idx.cpu().numpy()
     ref = oracle.select_ex(synth.to_bits(w.q), synth.to_bits(w.k), w.cu_q, w.cu_kv, w.cu_k, pool_w, forced_tail, head_sum)
-    if not np.array_equal(got, ref):
-        bad = np.argwhere(got != ref)
-        h, t = bad[0]
-        raise AssertionError(f"{len(bad)} of {ref.size} indices differ; first at head {h}, slot {t}: "
-                             f"gpu {got[h, t]} oracle {ref[h, t]}")
+    run_select_in_every_form(dw, ref, lambda: dw.select_ex(pool_w, forced_tail, head_sum))
     return dw, ref
 
 
