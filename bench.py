@@ -268,9 +268,10 @@ def main():
         return args.only in ("all", group)
 
     REUSE = ("select_reuse", "attend_reuse", "pack_reuse", "attend_packed_reuse", "attend_shared_list_reuse",
-             "select_pool3_reuse", "select_forced32_reuse", "select_headsum_reuse")
+             "select_pool3_reuse", "select_forced32_reuse", "select_headsum_reuse", "select_reuse_one_launch")
     REFRESH = ("dense_refresh", "dense_refresh_zero_inputs")
-    MIXED = ("select_mixed", "attend_mixed", "attend_mixed_reuse_part_alone", "attend_mixed_refresh_part_alone")
+    MIXED = ("select_mixed", "attend_mixed", "attend_mixed_reuse_part_alone", "attend_mixed_refresh_part_alone",
+             "select_mixed_two_launches")
     SMALL = ("select_c1", "attend_c1", "select_c2", "attend_c2")
     reuse, refresh, mixed = wanted("reuse", REUSE), wanted("refresh", REFRESH), wanted("mixed", MIXED)
     small = wanted("small", SMALL) if only_calls else args.only == "all"
@@ -289,6 +290,14 @@ def main():
     def add(name, fns):
         calls[name] = Train(name, fns)
 
+    def in_form(form, fn):
+        """fn with selection forced into one of its two forms (the library chooses by shape otherwise)"""
+        def run():
+            hcsa.dllm_hcsa_set_select_form(form)
+            fn()
+            hcsa.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_AUTO)
+        return run
+
     if reuse:
         ws3s = ws(hcsa.dllm_hcsa_select_workspace(d3[0].batch, d3[0].max_k))
         ws3a = ws(hcsa.dllm_hcsa_attend_workspace(d3[0].batch, d3[0].max_k))
@@ -303,6 +312,8 @@ def main():
             d.pack()
         add("attend_reuse", [lambda d=d: d.attend(workspace=ws3a) for d in d3])
         add("select_reuse", [lambda d=d: d.select(workspace=ws3s) for d in d3])
+        add("select_reuse_one_launch", [in_form(hcsa.DLLM_SELECT_FORM_ONE_LAUNCH, lambda d=d, out=out: hcsa.dllm_hcsa_select(
+            d.batch, d.cu_k, d.total_k, d.max_k, out, workspace=ws3s)) for d, out in zip(d3, scratch_idx)])
         add("pack_reuse", [lambda d=d: d.pack() for d in d3])
         add("attend_packed_reuse", [lambda d=d: d.attend_packed(workspace=ws3a) for d in d3])
         add("attend_shared_list_reuse", [lambda d=d, sh=sh: d.attend(sh, workspace=ws3a) for d, sh in zip(d3, shared)])
@@ -330,6 +341,8 @@ def main():
         torch.cuda.synchronize()
         union_bytes = gqa_union_bytes(w5, d5[0].idx)
         add("select_mixed", [lambda d=d: d.select(workspace=ws5s) for d in d5])
+        add("select_mixed_two_launches", [in_form(hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES, lambda d=d: d.select(workspace=ws5s))
+                                          for d in d5])
         add("attend_mixed", [lambda d=d: d.attend(workspace=ws5a) for d in d5])
         # each part of the mixed batch as a batch of its own, against its own roofline
         w5s = synth.subset(w5, np.flatnonzero(w5.seq_mode == 0), "c5_reuse_part")
@@ -351,7 +364,7 @@ def main():
                 d.select(workspace=wss)
             add(f"select_{tag}", [lambda d=d, wss=wss: d.select(workspace=wss) for d in ds])
             add(f"attend_{tag}", [lambda d=d, wsa=wsa: d.attend(workspace=wsa) for d in ds])
-    names = REUSE[:5] + REFRESH[:1] + MIXED + REUSE[5:] + REFRESH[1:] + SMALL
+    names = REUSE[:5] + REFRESH[:1] + MIXED[:4] + REUSE[5:] + MIXED[4:] + REFRESH[1:] + SMALL
     order = [calls[n] for n in names if n in calls and (not only_calls or n in only_calls)]
     # what BASELINE's metric counts as the step: the whole hot path on the three workloads
     step_calls = ("select_reuse", "attend_reuse", "dense_refresh", "select_mixed", "attend_mixed")
@@ -479,6 +492,10 @@ def main():
         # selection with its options on the Reuse workload (same algorithmic bytes as the plain call)
         "reuse_select_options_gbps": {n: rate_gbps(w3.select_bytes(), n)
                                       for n in ("select_pool3_reuse", "select_forced32_reuse", "select_headsum_reuse")},
+        # selection in the form the library does not choose for the workload: one launch on the ragged Reuse batch
+        # (it takes two there), two launches on the mixed grouped-query burst (it takes one there)
+        "select_other_form_gbps": {"select_reuse_one_launch": rate_gbps(w3.select_bytes(), "select_reuse_one_launch"),
+                                   "select_mixed_two_launches": rate_gbps(w5.select_bytes(), "select_mixed_two_launches")},
         # the small configurations: microseconds per call (launch latency, not a bandwidth)
         "small_config_call_us": {n: round(T[n][0] * 1e3, 2) for n in SMALL if n in T},
         "call_ms_mean_min_median": {k: [round(x, 5) for x in v] for k, v in T.items()},
@@ -491,7 +508,7 @@ def main():
                                "attend_sparse_multi_bf16_kernel", w3.attend_sparse_bytes()),
         "roofline_select": roof("hbm", select_gbps, HBM_PEAK_GBPS, "GB/s", "select_reuse", "score_kernel",
                                 w3.select_bytes()),
-        "roofline_select_mixed": roof("hbm", mixed_sel_gbps, HBM_PEAK_GBPS, "GB/s", "select_mixed", "score_kernel",
+        "roofline_select_mixed": roof("hbm", mixed_sel_gbps, HBM_PEAK_GBPS, "GB/s", "select_mixed", "select_fused_kernel",
                                       w5.select_bytes()),
         "peaks": {"hbm_GBps": HBM_PEAK_GBPS, "mfma_bf16_dense_TFLOPs": MFMA_BF16_PEAK_TFLOPS},
         "measured_ceilings_context": MEASURED_CEILINGS,

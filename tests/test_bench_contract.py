@@ -94,7 +94,7 @@ def test_traffic_file_and_summary_agree_and_cover_the_roofline_kernels():
     traffic = bench.load_traffic()
     assert traffic == data["calls"]
     for call, kernel in (("dense_refresh", "attend_dense_bf16_kernel"), ("attend_reuse", "attend_sparse_multi_bf16_kernel"),
-                         ("select_reuse", "score_kernel"), ("select_mixed", "score_kernel")):
+                         ("select_reuse", "score_kernel"), ("select_mixed", "select_fused_kernel")):
         total = bench.traffic_of(traffic, call, kernel)
         assert total is not None and total > 0
     # the figures are measured traffic of these workloads: within a few percent of the algorithmic bytes
@@ -102,6 +102,7 @@ def test_traffic_file_and_summary_agree_and_cover_the_roofline_kernels():
     w3 = synth.config(3)
     assert 0.95 < bench.traffic_of(traffic, "attend_reuse", "attend_sparse_multi") / w3.attend_sparse_bytes() < 1.05
     assert 0.95 < bench.traffic_of(traffic, "select_reuse", "score_kernel") / w3.select_bytes() < 1.05
+    assert 0.98 < bench.traffic_of(traffic, "select_mixed", "select_fused_kernel") / synth.config(5).select_bytes() < 1.02
 
 
 @pytest.mark.gpu
