@@ -34,6 +34,22 @@ constexpr int kMaxTilesPerWave = 16;  // chunk_rows <= kMaxTilesPerWave * kWaves
 #define DLLM_SPARSE_DEPTH 1
 #endif
 constexpr int kDepth = DLLM_SPARSE_DEPTH;   // tiles of gathered rows a wave keeps in flight in registers
+// The k-th tile wave `wave` takes of a pass after its first (tile w is wave w's first).  Two waves share
+// a SIMD and the older one (waves 0-3) wins the arbitration for memory instructions, so with equal
+// shares four waves finish early and wait at the merge.  The later tiles are therefore dealt in periods
+// of 20 of which each of waves 0-3 takes three and each of waves 4-7 two, always the same ones, so the
+// result does not depend on timing (measured on the batched Reuse workload: 40.9 -> 39.9 us; 4 : 3 and a
+// shared counter that deals tiles as waves come free measure the same, 5 : 4 and 2 : 1 less).
+__device__ __forceinline__ int later_tile(int wave, int k) {
+  constexpr int F = 3, S = 2, P = 4 * (F + S);
+  // rounds of a period: the first S rounds go to all eight waves, the other F - S to waves 0-3 only
+  if (wave < 4) {
+    const int p = k / F, r = k % F;
+    return kWavesMulti + P * p + (r < S ? 8 * r + wave : 8 * S + 4 * (r - S) + wave);
+  }
+  const int p = k / S, r = k % S;
+  return kWavesMulti + P * p + 8 * r + wave;
+}
 constexpr int kRankBatch = 64;        // batches up to this size are walked longest kept list first
 
 // A (sequence, head) with kb kept rows is cut into n = ceil(kb / chunk_rows) chunks of equal size
@@ -541,11 +557,11 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
     asm volatile("" : "+v"(x));
     return x;
   };
-  // gather tile j of this wave in pass p
-  auto fetch = [&](v4u (&kr)[NLD], v4u (&vr)[NLD], const Pass& p, int bf, int j) {
+  // gather tile `tile` of pass p (its ids lie where the wave tile % WAVES put them)
+  auto fetch = [&](v4u (&kr)[NLD], v4u (&vr)[NLD], const Pass& p, int bf, int tile) {
     if constexpr (STREAM) {
-      // rows c0 + (wave + j * WAVES) * 32 ..: positions past the end repeat the last row (masked in the softmax)
-      const int first = p.c0 + (wave + j * WAVES) * kTile;
+      // rows c0 + tile * 32 ..: positions past the end repeat the last row (masked in the softmax)
+      const int first = p.c0 + tile * kTile;
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
         const uint32_t off = __umul24(uint32_t(min(first + (i * 64 + lane) / CH, p.c1 - 1)), pitch) + coff;
@@ -553,10 +569,10 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
         vr[i] = load_once(p.vbase + off);
       }
     } else {
-      const int* my_rows = sm_rows[bf][wave];
+      const int* my_rows = sm_rows[bf][tile % WAVES] + (tile / WAVES) * kTile;
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const uint32_t off = __umul24(uint32_t(my_rows[j * kTile + (i * 64 + lane) / CH]), pitch) + coff;
+        const uint32_t off = __umul24(uint32_t(my_rows[(i * 64 + lane) / CH]), pitch) + coff;
         kr[i] = load_once(p.kbase + off);
         vr[i] = load_once(p.vbase + off);
       }
@@ -568,13 +584,13 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
   int bf = 0;
   v4u kra[NLD], vra[NLD];
   if constexpr (STREAM) {   // nothing to wait for before the first rows are asked for
-    if (wave < cur.ntiles) fetch(kra, vra, cur, 0, 0);
+    if (wave < cur.ntiles) fetch(kra, vra, cur, 0, wave);
     prefetch(cur, 0);
     wait_tile_loads();
   } else {
     prefetch(cur, 0);
     wait_tile_loads();
-    if (wave < cur.ntiles) fetch(kra, vra, cur, 0, 0);
+    if (wave < cur.ntiles) fetch(kra, vra, cur, 0, wave);
   }
   __syncthreads();   // the queries are in place
   for (;;) {
@@ -585,7 +601,7 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
     auto start_next = [&]() {
       if (more) {
         wait_tile_loads();   // the next pass's ids (nothing else is outstanding here)
-        if (wave < nxt.ntiles) fetch(kra, vra, nxt, bf ^ 1, 0);
+        if (wave < nxt.ntiles) fetch(kra, vra, nxt, bf ^ 1, wave);
       }
     };
     float m_used = -INFINITY, lsum = 0.0f;
@@ -595,7 +611,11 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[db][i] = 0.0f;
     if (wave >= cur.ntiles) start_next();
-    for (int j = 0, tile = wave; tile < cur.ntiles; ++j, tile += WAVES) {
+    // A wave's first tile of a pass is tile `wave` (gathered before the pass starts, from ids the wave
+    // loaded itself); the later ones (later_tile) may have ids another wave loaded, which are in place:
+    // every wave waited for its id loads before the barrier that opened this pass.
+    int taken = 0;   // tiles of this pass this wave has taken after its first
+    for (int tile = wave; tile < cur.ntiles;) {
       KAddr<D> kar;
       kar.base = opaque(ka.base);
       VtAddr<D> vtr;
@@ -608,7 +628,8 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
         *reinterpret_cast<v4u*>(ktile + woff) = kra[i];
         *reinterpret_cast<v4u*>(vtile + woff) = vra[i];
       }
-      if (tile + WAVES < cur.ntiles) fetch(kra, vra, cur, bf, j + 1);
+      const int next = later_tile(wave, taken++);
+      if (next < cur.ntiles) fetch(kra, vra, cur, bf, next);
       else start_next();
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -616,6 +637,7 @@ __global__ __launch_bounds__(kWavesMulti * 64, 1) void attend_sparse_multi_bf16_
       sparse_tile_math<D>(ktile, vtile, qtile[bf], kar, vtr, hf, cur.c1 - (cur.c0 + tile * kTile), zscale, m_used,
                           lsum, acc);
       __builtin_amdgcn_wave_barrier();
+      tile = next;
     }
 
     // ---- merge the eight waves' (m, l, O^T) through LDS (see attend_sparse_bf16_kernel)
