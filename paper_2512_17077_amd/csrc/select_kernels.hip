@@ -603,8 +603,8 @@ __global__ __launch_bounds__(T) void topk_reg_kernel(
 // ------------------------------------------------------------------ scores and top-k in one workgroup
 // One workgroup per (sequence, KV head) walks the head's whole K column once, keeps the keys of its
 // GT query heads in registers (one key per lane, tile and head) and ranks them there: the scores never
-// travel to HBM and back and the lists need no second launch.  Lists of up to kFusedWaves * kFusedTiles
-// * 64 positions; the arithmetic, the tie rule and the output order are those of the kernels above.
+// travel to HBM and back and the lists need no second launch.  Lists of up to kFusedWords * 64
+// positions; the arithmetic, the tie rule and the output order are those of the kernels above.
 //
 // Ranking is a radix select over digits of 10, 11 and 11 bits.  The first histogram is counted while
 // the column streams in (its atomics hide under the memory waits); the other two count only the keys
@@ -612,19 +612,24 @@ __global__ __launch_bounds__(T) void topk_reg_kernel(
 // kept keys only.  Each head's histogram is scanned by one wave, in two levels (a lane sums a run of
 // bins, the owner's run is then looked at one bin per lane).  Compaction goes through a bitmap of the
 // kept positions (see there).
-constexpr int kFusedWaves = 8, kFusedTiles = 16;
-typedef __attribute__((ext_vector_type(16))) uint32_t u32x16;
+constexpr int kFusedWords = 128;   // 64-row tiles per list at most (8192 positions): W waves of kFusedWords / W tiles
+// Eight waves of 16 tiles for every group size.  (Four waves of 32 tiles for one or two query heads per
+// KV head, so that two workgroups share a compute unit and one's start-up and ranking run under the
+// other's streaming, measured 2-10 % slower on every batch tried.)
+template <int GT> constexpr int fused_waves() { return 8; }
+template <int N> struct KeyVec { typedef __attribute__((ext_vector_type(N))) uint32_t type; };
 constexpr int kBinsA = 1024, kBinsB = 2048;   // digits: key >> 22, (key >> 11) & 2047, key & 2047
 
 template <int ES, int D, int GT>
 struct FusedLds {   // byte offsets inside the workgroup's dynamic LDS
-  static constexpr size_t stage = size_t(kFusedWaves) * 64 * D * ES;            // the waves' tiles while streaming
+  static constexpr int W = fused_waves<GT>();
+  static constexpr size_t stage = size_t(W) * 64 * D * ES;            // the waves' tiles while streaming
   static constexpr size_t hist_bc = size_t(GT) * 2 * kBinsB * 4;                // afterwards: second and third histograms
-  static constexpr size_t kept = size_t(GT) * kFusedWaves * kFusedTiles * 64 * 4;   // at the end: the kept positions [GT][8192]
+  static constexpr size_t kept = size_t(GT) * kFusedWords * 64 * 4;                 // at the end: the kept positions [GT][8192]
   static constexpr size_t region0 = stage > hist_bc ? (stage > kept ? stage : kept) : (hist_bc > kept ? hist_bc : kept);
   static constexpr size_t off_a = region0;                                      // first histogram [GT][kBinsA]
   static constexpr size_t off_counts = off_a + size_t(GT) * kBinsA * 4;         // two bitmaps [GT][waves * tiles] of 64 bits, [2][waves] totals
-  static constexpr size_t off_res = off_counts + size_t(GT) * kFusedWaves * kFusedTiles * 16 + 2 * kFusedWaves * 4;   // [GT][4]
+  static constexpr size_t off_res = off_counts + size_t(GT) * kFusedWords * 16 + 2 * 8 * 4;   // [GT][4]
   static constexpr size_t off_sums = off_res + size_t(GT) * 16;                 // [GT][D]
   static constexpr size_t bytes = off_sums + size_t(GT) * D * 4;
 };
@@ -661,13 +666,13 @@ __device__ __forceinline__ uint3 pick_bin(const uint32_t* hrow, uint32_t kth, in
 __device__ __forceinline__ void set_lane(uint32_t& v, uint32_t x, int u) { v = int(threadIdx.x & 63) == u ? x : v; }
 
 template <int ES, int D, int GT>
-__global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void select_fused_kernel(
+__global__ __launch_bounds__(fused_waves<GT>() * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void select_fused_kernel(
     const char* __restrict__ k, const char* __restrict__ q, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k, int32_t total_k, int32_t forced_tail,
-    int32_t* __restrict__ idx_out, Shape s DLLM_CHECK_PARAM) {
+    int32_t ranked, int32_t* __restrict__ idx_out, Shape s DLLM_CHECK_PARAM) {
   DLLM_CHECK_EXIT();
-  constexpr int ROWB = D * ES, CH = ROWB / 16, EPC = 16 / ES, W = kFusedWaves, NT = kFusedTiles, T = W * 64;
-  static_assert(NT == 16 && W * NT == 128, "sixteen tiles per wave, two (wave, tile) counts per lane");
+  constexpr int ROWB = D * ES, CH = ROWB / 16, EPC = 16 / ES, W = fused_waves<GT>(), NT = kFusedWords / W, T = W * 64;
+  static_assert(NT <= 32, "a wave's tile masks are collected one per lane, its keys in one register vector per head");
   static_assert(GT <= W, "one wave scans one head's histogram");
   using Lds = FusedLds<ES, D, GT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -678,9 +683,31 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
   uint32_t* res = reinterpret_cast<uint32_t*>(lds + Lds::off_res);
   float* sums = reinterpret_cast<float*>(lds + Lds::off_sums);
 
-  const int b = blockIdx.x / s.hkv, g = (blockIdx.x + b) % s.hkv;   // (rotation: see score_kernel)
-  int ck0 = cu_k[b], ck1 = cu_k[b + 1], kv0 = cu_kv[b], kv1 = cu_kv[b + 1], q0 = cu_q[b], q1 = cu_q[b + 1];
-  asm volatile("" : "+s"(ck0), "+s"(ck1), "+s"(kv0), "+s"(kv1), "+s"(q0), "+s"(q1));
+  // Which sequence: slot blockIdx.x / hkv.  When the workgroups run in several rounds (`ranked`, batches
+  // of up to 64 sequences) the slots go down the sequences by length, longest first: workgroups start in
+  // the order of their numbers, so the compute units that come free first pick up the longest lists
+  // left and the rounds end level whatever the mix of lengths.
+  int b = blockIdx.x / s.hkv;
+  int ck0, ck1, kv0, kv1, q0, q1;
+  if (ranked) {
+    const int ln = threadIdx.x & 63, i = min(ln, s.batch - 1);
+    const int a0 = cu_k[i], a1 = cu_k[i + 1], b0 = cu_kv[i], b1 = cu_kv[i + 1], c0 = cu_q[i], c1 = cu_q[i + 1];
+    const int mine = ln < s.batch ? (a1 == a0 ? -1 : b1 - b0) : -2;   // (a sequence that is not scored has no length)
+    int rank = 0;
+    for (int j = 0; j < s.batch; ++j) {
+      const int other = __builtin_amdgcn_readlane(mine, j);
+      rank += (other > mine) || (other == mine && j < ln);
+    }
+    const uint64_t hit = __ballot(ln < s.batch && rank == b);   // exactly one lane: the ranks are a permutation
+    b = hit ? __builtin_ctzll(hit) : 0;
+    ck0 = __builtin_amdgcn_readlane(a0, b); ck1 = __builtin_amdgcn_readlane(a1, b);
+    kv0 = __builtin_amdgcn_readlane(b0, b); kv1 = __builtin_amdgcn_readlane(b1, b);
+    q0 = __builtin_amdgcn_readlane(c0, b); q1 = __builtin_amdgcn_readlane(c1, b);
+  } else {
+    ck0 = cu_k[b]; ck1 = cu_k[b + 1]; kv0 = cu_kv[b]; kv1 = cu_kv[b + 1]; q0 = cu_q[b]; q1 = cu_q[b + 1];
+    asm volatile("" : "+s"(ck0), "+s"(ck1), "+s"(kv0), "+s"(kv1), "+s"(q0), "+s"(q1));
+  }
+  const int g = (blockIdx.x + b) % s.hkv;   // (rotation: see score_kernel)
   if (ck1 == ck0) return;
   const int L = kv1 - kv0, Lc = L - forced_tail, kb = ck1 - ck0 - forced_tail;
   if (kb < 0 || Lc < kb) return;   // broken precondition (see topk_kernel): write nothing
@@ -746,7 +773,8 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
 
   // key of tile u for head t in k<t>[u]; 0, below every real key, where there is no position
   // (four named vectors: an array of them is not kept in registers)
-  u32x16 k0 = u32x16(0u), k1 = k0, k2 = k0, k3 = k0;
+  typedef typename KeyVec<NT>::type keyvec;
+  keyvec k0 = keyvec(0u), k1 = k0, k2 = k0, k3 = k0;
   for (int it = 0; it < ntiles; ++it) {
     const int r0 = first + it * 64;
 #pragma unroll
@@ -872,8 +900,8 @@ __global__ __launch_bounds__(kFusedWaves * 64) __attribute__((amdgpu_waves_per_e
   // lists go out in whole lines.  Keys equal to the threshold have a bitmap of their own, used only
   // when not all of them are kept (scores that tie exactly): a word then keeps its first few equal
   // keys, as many as the rule "lower position first" leaves for it.
-  static_assert(T == 4 * 128 && GT <= 4, "one thread per tile of each of up to four heads");
-  constexpr int kWords = W * NT;   // tiles, and so bitmap words, per head
+  static_assert(GT * kFusedWords <= T && W <= 8, "one thread per tile of each head; the waves' totals fit wave_tot");
+  constexpr int kWords = kFusedWords;   // tiles, and so bitmap words, per head
   uint64_t* bitmap = reinterpret_cast<uint64_t*>(lds + Lds::off_counts);   // [GT][kWords] keys above the threshold
   uint64_t* bitmap_eq = bitmap + GT * kWords;                              // [GT][kWords] keys equal to it
   uint32_t* wave_tot = reinterpret_cast<uint32_t*>(bitmap_eq + GT * kWords);   // [2][W]
@@ -990,15 +1018,18 @@ static bool fused_can(const Shape& s, dllm_dtype dt, int32_t pool_w, int32_t hea
   if (pool_w != 1 || head_sum) return false;
   if (s.group != 1 && s.group != 2 && s.group != 4) return false;
   if (s.d * (dt == DLLM_BF16 ? 2 : 4) > 256) return false;
-  return s.max_kv <= kFusedWaves * kFusedTiles * 64;
+  return s.max_kv <= kFusedWords * 64;
 }
 // ... and where it pays (measured on batches of equal lists, 1 to 4 query heads per KV head, lists of
 // 2048 to 8192): each (sequence, KV head) pair is one workgroup that takes most of a compute unit's
 // LDS, so the pairs run in rounds of one per compute unit.  The form wins by 5 to 30 % when the last
 // round is mostly full, three quarters of the compute units in a single round, four fifths when there
 // are several, and loses up to 2x when a few pairs leave most of the chip idle.  Lists of very
-// different lengths make the rounds uneven (measured: 2 % slower on 16 sequences of 770 to 3411
-// positions), so the batch must also be fairly even: mean length at least 3/4 of the longest.
+// different lengths make the rounds uneven, so the batch must also be fairly even (mean length at least
+// 3/4 of the longest).  Walking the sequences longest first (see the kernel) makes up for most of that
+// when there are several rounds, but not more: on 16 sequences of 770 to 3411 positions the two forms
+// then tie (54.9 against 55.9 us in one harness, 56.3 against 54.9 us in the other; 56.2 us in batch
+// order), so such batches keep two launches.
 static int compute_units() {
   static std::atomic<int> cached{0};
   int n = cached.load();
@@ -1023,17 +1054,18 @@ static hipError_t launch_fused(const Shape& s, const void* k, const void* q, con
                                const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t forced_tail,
                                int32_t* idx_out, hipStream_t st) {
   const char *kp = static_cast<const char*>(k), *qp = static_cast<const char*>(q);
-  auto launch = [&](auto kernel, size_t lds) -> hipError_t {
+  auto launch = [&](auto kernel, size_t lds, int waves) -> hipError_t {
     const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, int(lds));
     if (ea != hipSuccess) return ea;
-    kernel<<<dim3(s.batch * s.hkv), dim3(kFusedWaves * 64), lds, st>>>(kp, qp, cu_q, cu_kv, cu_k, total_k, forced_tail,
-                                                                      idx_out, s DLLM_CHECK_PASS);
+    const int32_t ranked = s.batch <= 64 && int64_t(s.batch) * s.hkv > compute_units() ? 1 : 0;
+    kernel<<<dim3(s.batch * s.hkv), dim3(waves * 64), lds, st>>>(kp, qp, cu_q, cu_kv, cu_k, total_k, forced_tail,
+                                                                      ranked, idx_out, s DLLM_CHECK_PASS);
     return hipGetLastError();
   };
-  if (s.group == 4) return launch(select_fused_kernel<ES, D, 4>, FusedLds<ES, D, 4>::bytes);
-  if (s.group == 2) return launch(select_fused_kernel<ES, D, 2>, FusedLds<ES, D, 2>::bytes);
-  return launch(select_fused_kernel<ES, D, 1>, FusedLds<ES, D, 1>::bytes);
+  if (s.group == 4) return launch(select_fused_kernel<ES, D, 4>, FusedLds<ES, D, 4>::bytes, fused_waves<4>());
+  if (s.group == 2) return launch(select_fused_kernel<ES, D, 2>, FusedLds<ES, D, 2>::bytes, fused_waves<2>());
+  return launch(select_fused_kernel<ES, D, 1>, FusedLds<ES, D, 1>::bytes, fused_waves<1>());
 }
 
 hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,

@@ -159,8 +159,14 @@ def test_select_in_one_launch_edges(dtype, Hq, Hkv, D):
         off += L
     check_select(w, name="edges, rows repeated every 40 positions")
     check_select_ex(w, 1, 1, False, "edges, forced block of 1 on repeated rows")
-    many = custom(42, dtype, Hq, 4 * Hkv if Hq % (4 * Hkv) == 0 else Hkv, D, [700] * 80, [32] * 80, [70] * 80)
+    # several rounds of workgroups: 80 sequences are taken in batch order, up to 64 longest list first
+    many = custom(42, dtype, 8, 8, D, [700] * 80, [32] * 80, [70] * 80)
     check_select(many, name="more pairs than compute units")
+    rng = np.random.default_rng(43)
+    lens64 = [int(x) for x in rng.integers(1, 1500, size=64)]
+    keep64 = [int(rng.integers(0, L + 1)) for L in lens64]      # (some sequences are not scored at all)
+    ragged = custom(43, dtype, 8, 8, D, lens64, [32] * 64, keep64)
+    check_select(ragged, name="64 ragged sequences, more pairs than compute units")
 
 
 @pytest.mark.parametrize("dtype,Hq,Hkv,D", [(torch.bfloat16, 32, 8, 128), (torch.bfloat16, 16, 16, 64),
