@@ -691,7 +691,8 @@ def test_attend_without_cu_k_zeroes_every_sequence_not_flagged_dense(dtype):
 
 # ------------------------------------------------------------------ HIP graph capture
 
-@pytest.mark.parametrize("which_workload", ["layer-shaped config 2", "ragged batch (config 3 / 4)"])
+@pytest.mark.parametrize("which_workload", ["layer-shaped config 2", "ragged batch (config 3 / 4)",
+                                            "layer-shaped config 2, selection in one launch"])
 def test_select_and_attend_replayed_from_a_hip_graph(which_workload):
     """A serving loop captures the launch-bound step once and replays it.  The library allocates
     nothing, clears nothing with memsets and never synchronises, so a captured select + attend must
@@ -700,6 +701,15 @@ def test_select_and_attend_replayed_from_a_hip_graph(which_workload):
     compute units and takes the multi-list attend kernel."""
     w = synth.config(2) if which_workload.startswith("layer") else synth.config(3, scale_down=4)
     dw = workload.DeviceWorkload(w)
+    if which_workload.endswith("one launch"):
+        hcsa.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_ONE_LAUNCH)
+    try:
+        replay_select_and_attend(w, dw, which_workload)
+    finally:
+        hcsa.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_AUTO)
+
+
+def replay_select_and_attend(w, dw, which_workload):
     wss = torch.empty(max(256, hcsa.dllm_hcsa_select_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
     wsa = torch.empty(max(256, hcsa.dllm_hcsa_attend_workspace(dw.batch, dw.max_k)), dtype=torch.uint8, device=dw.device)
     q_a = dw.q.clone()
