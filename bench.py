@@ -271,7 +271,7 @@ def main():
              "select_pool3_reuse", "select_forced32_reuse", "select_headsum_reuse", "select_reuse_one_launch")
     REFRESH = ("dense_refresh", "dense_refresh_zero_inputs")
     MIXED = ("select_mixed", "attend_mixed", "attend_mixed_reuse_part_alone", "attend_mixed_refresh_part_alone",
-             "select_mixed_two_launches")
+             "select_mixed_two_launches", "select_pool3_mixed")
     SMALL = ("select_c1", "attend_c1", "select_c2", "attend_c2")
     reuse, refresh, mixed = wanted("reuse", REUSE), wanted("refresh", REFRESH), wanted("mixed", MIXED)
     small = wanted("small", SMALL) if only_calls else args.only == "all"
@@ -343,6 +343,10 @@ def main():
         add("select_mixed", [lambda d=d: d.select(workspace=ws5s) for d in d5])
         add("select_mixed_two_launches", [in_form(hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES, lambda d=d: d.select(workspace=ws5s))
                                           for d in d5])
+        # the paper's default pooling window (Table 2) on the grouped-query workload; results go to a scratch list
+        pool_idx = [torch.empty_like(d.idx) for d in d5]
+        add("select_pool3_mixed", [lambda d=d, out=out: hcsa.dllm_hcsa_select(d.batch, d.cu_k, d.total_k, d.max_k, out, 3,
+                                                                               workspace=ws5s) for d, out in zip(d5, pool_idx)])
         add("attend_mixed", [lambda d=d: d.attend(workspace=ws5a) for d in d5])
         # each part of the mixed batch as a batch of its own, against its own roofline
         w5s = synth.subset(w5, np.flatnonzero(w5.seq_mode == 0), "c5_reuse_part")
@@ -496,6 +500,7 @@ def main():
         # (it takes two there), two launches on the mixed grouped-query burst (it takes one there)
         "select_other_form_gbps": {"select_reuse_one_launch": rate_gbps(w3.select_bytes(), "select_reuse_one_launch"),
                                    "select_mixed_two_launches": rate_gbps(w5.select_bytes(), "select_mixed_two_launches")},
+        "mixed_select_pool3_gbps": rate_gbps(w5.select_bytes(), "select_pool3_mixed"),
         # the small configurations: microseconds per call (launch latency, not a bandwidth)
         "small_config_call_us": {n: round(T[n][0] * 1e3, 2) for n in SMALL if n in T},
         "call_ms_mean_min_median": {k: [round(x, 5) for x in v] for k, v in T.items()},

@@ -136,14 +136,15 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch *batch,
  * Selection runs in one of two forms with identical results.  Two launches: a pass over K writes every
  * fp32 score to the workspace, then one workgroup per list ranks them (any shape).  One launch: one
  * workgroup per (sequence, KV head) walks the head's column of K once, keeps the keys of the head's
- * query heads in registers and ranks them there, so no score travels through HBM; it takes plain
- * per-head selection (pool_w = 1, head_sum = 0) of lists of up to 8192 positions with 1, 2 or 4 query
- * heads per KV head and rows of up to 256 bytes.  By default the library takes the one-launch form when
- * the shape allows it, the (sequence, KV head) pairs fill the compute units in whole rounds or nearly
- * (at least 3/4 of them in a single round, 4/5 of the last of several) and the batch is fairly even
- * (total_kv >= 3/4 * batch * max_kv), where it measures 5 to 30 % faster.  This call overrides that choice for the whole process (all threads, all later
- * calls); it exists for measurement and for tests that must reach both forms.  Returns the previous
- * setting, or -1 (and changes nothing) for a value that is none of the three.
+ * query heads in registers and ranks them there, so no score travels through HBM; it takes per-head
+ * selection (head_sum = 0; any pooling window, with or without a forced block) of lists of up to 8192
+ * positions with 1, 2 or 4 query heads per KV head and rows of up to 256 bytes.  By default the
+ * library takes the one-launch form when the shape allows it, the (sequence, KV head) pairs fill the
+ * compute units in whole rounds or nearly (at least 3/4 of them in a single round, 4/5 of the last of
+ * several) and the batch is fairly even (total_kv >= 3/4 * batch * max_kv), where it measures 5 to
+ * 30 % faster.  This call overrides that choice for the whole process (all threads, all later calls);
+ * it exists for measurement and for tests that must reach both forms.  Returns the previous setting,
+ * or -1 (and changes nothing) for a value that is none of the three.
  */
 #define DLLM_SELECT_FORM_AUTO 0
 #define DLLM_SELECT_FORM_TWO_LAUNCHES 1

@@ -612,6 +612,8 @@ __global__ __launch_bounds__(T) void topk_reg_kernel(
 // kept keys only.  Each head's histogram is scanned by one wave, in two levels (a lane sums a run of
 // bins, the owner's run is then looked at one bin per lane).  Compaction goes through a bitmap of the
 // kept positions (see there).
+// With a pooling window the keys are max-pooled in the registers once the column is in (see there); the
+// first histogram is then counted afterwards, in the open.
 constexpr int kFusedWords = 128;   // 64-row tiles per list at most (8192 positions): W waves of kFusedWords / W tiles
 // Eight waves of 16 tiles for every group size.  (Four waves of 32 tiles for one or two query heads per
 // KV head, so that two workgroups share a compute unit and one's start-up and ranking run under the
@@ -669,7 +671,7 @@ template <int ES, int D, int GT>
 __global__ __launch_bounds__(fused_waves<GT>() * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void select_fused_kernel(
     const char* __restrict__ k, const char* __restrict__ q, const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ cu_kv, const int32_t* __restrict__ cu_k, int32_t total_k, int32_t forced_tail,
-    int32_t ranked, int32_t* __restrict__ idx_out, Shape s DLLM_CHECK_PARAM) {
+    int32_t pool_w, int32_t ranked, int32_t* __restrict__ idx_out, Shape s DLLM_CHECK_PARAM) {
   DLLM_CHECK_EXIT();
   constexpr int ROWB = D * ES, CH = ROWB / 16, EPC = 16 / ES, W = fused_waves<GT>(), NT = kFusedWords / W, T = W * 64;
   static_assert(NT <= 32, "a wave's tile masks are collected one per lane, its keys in one register vector per head");
@@ -771,6 +773,7 @@ __global__ __launch_bounds__(fused_waves<GT>() * 64) __attribute__((amdgpu_waves
       for (int i = 0; i < NQ; ++i) vq[t][i] = qs[t * D + 16 * i];
   }
 
+  const int half = pool_w >> 1;   // pooling window (Section 4.5 Eq. 6): positions p - half .. p + half, clipped to the candidates
   // key of tile u for head t in k<t>[u]; 0, below every real key, where there is no position
   // (four named vectors: an array of them is not kept in registers)
   typedef typename KeyVec<NT>::type keyvec;
@@ -809,7 +812,7 @@ __global__ __launch_bounds__(fused_waves<GT>() * 64) __attribute__((amdgpu_waves
 #pragma unroll
     for (int t = 0; t < GT; ++t) {
       key[t] = valid ? order_key(acc[t] + 0.0f) : 0u;
-      if (valid) atomicAdd(&hist_a[t * kBinsA + (key[t] >> 22)], 1u);
+      if (valid && half == 0) atomicAdd(&hist_a[t * kBinsA + (key[t] >> 22)], 1u);   // (pooled keys are counted once they exist)
     }
     k0[it] = key[0];
     if constexpr (GT > 1) k1[it] = key[1];
@@ -827,6 +830,76 @@ __global__ __launch_bounds__(fused_waves<GT>() * 64) __attribute__((amdgpu_waves
     key[0][u] = k0[u];
     if constexpr (GT > 1) key[1][u] = k1[u];
     if constexpr (GT > 2) { key[2][u] = k2[u]; key[3][u] = k3[u]; }
+  }
+
+  if (half > 0) {
+    // Max-pool the keys over the window (the key map is monotone, so this pools the scores).  A wave's
+    // positions are consecutive, 64 per tile, so a neighbour is the next lane, across a tile edge the
+    // next tile's first or the previous tile's last lane, and across a wave's edge a key of the
+    // neighbouring wave: every wave leaves its first and its last tile in LDS for that.  The window is
+    // built one position at a time: the keys moved on by one more lane per step, to either side, and
+    // the running maximum.  Positions past the candidates hold key 0 and get it back at the end.
+    uint32_t* edge = reinterpret_cast<uint32_t*>(lds + Lds::hist_bc);   // [GT][W][first | last][64]
+    static_assert(Lds::hist_bc + size_t(GT) * W * 128 * 4 <= Lds::region0, "the waves' edge tiles fit beside the histograms");
+    const int last_u = max(ntiles - 1, 0);
+    edge[((0 * W + wave) * 2 + 0) * 64 + lane] = k0[0];
+    edge[((0 * W + wave) * 2 + 1) * 64 + lane] = k0[last_u];
+    if constexpr (GT > 1) {
+      edge[((1 * W + wave) * 2 + 0) * 64 + lane] = k1[0];
+      edge[((1 * W + wave) * 2 + 1) * 64 + lane] = k1[last_u];
+    }
+    if constexpr (GT > 2) {
+      edge[((2 * W + wave) * 2 + 0) * 64 + lane] = k2[0];
+      edge[((2 * W + wave) * 2 + 1) * 64 + lane] = k2[last_u];
+      edge[((3 * W + wave) * 2 + 0) * 64 + lane] = k3[0];
+      edge[((3 * W + wave) * 2 + 1) * 64 + lane] = k3[last_u];
+    }
+    __syncthreads();
+    // (a wave with tiles has a full run before it; the wave after it may have none: its tiles then hold key 0)
+    const bool has_prev = wave > 0 && ntiles > 0, has_next = wave + 1 < W && ntiles > 0;
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+      const uint32_t* prev_last = edge + ((t * W + max(wave - 1, 0)) * 2 + 1) * 64;
+      const uint32_t* next_first = edge + ((t * W + min(wave + 1, W - 1)) * 2 + 0) * 64;
+      uint32_t run[NT], best[NT];
+#pragma unroll
+      for (int u = 0; u < NT; ++u) run[u] = best[u] = key[t][u];
+      // (rotations by one lane, then the lane at the tile's edge takes the neighbouring tile's rotated
+      // value: no scalar register between two vector instructions)
+      for (int sh = 1; sh <= half; ++sh) {   // keys of positions p - sh
+        const uint32_t from_prev = has_prev ? prev_last[64 - sh] : 0u;
+        uint32_t rot = uint32_t(__builtin_amdgcn_update_dpp(0, int(run[NT - 1]), 0x13c, 0xf, 0xf, false));   // wave_ror:1
+#pragma unroll
+        for (int u = NT - 1; u >= 0; --u) {
+          const uint32_t below = u > 0 ? uint32_t(__builtin_amdgcn_update_dpp(0, int(run[u - 1]), 0x13c, 0xf, 0xf, false)) : from_prev;
+          run[u] = lane == 0 ? below : rot;   // (lane 0 of the rotated tile below holds that tile's lane 63)
+          best[u] = max(best[u], run[u]);
+          rot = below;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NT; ++u) run[u] = key[t][u];
+      for (int sh = 1; sh <= half; ++sh) {   // keys of positions p + sh
+        const uint32_t from_next = has_next ? next_first[sh - 1] : 0u;
+        uint32_t rot = uint32_t(__builtin_amdgcn_update_dpp(0, int(run[0]), 0x134, 0xf, 0xf, false));   // wave_rol:1
+#pragma unroll
+        for (int u = 0; u < NT; ++u) {
+          // the tile after this one: the next register, or the next wave's first tile after this wave's last
+          uint32_t above = 0;
+          if (u + 1 < NT) above = uint32_t(__builtin_amdgcn_update_dpp(0, int(run[u + 1]), 0x134, 0xf, 0xf, false));
+          run[u] = lane == 63 ? (u + 1 == ntiles ? from_next : above) : rot;
+          best[u] = max(best[u], run[u]);
+          rot = above;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NT; ++u) {
+        const bool valid = u < ntiles && first + u * 64 + lane < Lc;
+        key[t][u] = valid ? best[u] : 0u;
+        if (valid) atomicAdd(&hist_a[t * kBinsA + (key[t][u] >> 22)], 1u);
+      }
+    }
+    __syncthreads();
   }
 
   // wave w < GT scans the histogram of head w and leaves {bin, rank, count} for all
@@ -1015,7 +1088,8 @@ int32_t set_select_form(int32_t form) {
 
 // Shapes select_fused_kernel can take.
 static bool fused_can(const Shape& s, dllm_dtype dt, int32_t pool_w, int32_t head_sum) {
-  if (pool_w != 1 || head_sum) return false;
+  (void)pool_w;   // (any window the call accepts)
+  if (head_sum) return false;
   if (s.group != 1 && s.group != 2 && s.group != 4) return false;
   if (s.d * (dt == DLLM_BF16 ? 2 : 4) > 256) return false;
   return s.max_kv <= kFusedWords * 64;
@@ -1052,7 +1126,7 @@ static bool fused_pays(const Shape& s) {
 template <int ES, int D>
 static hipError_t launch_fused(const Shape& s, const void* k, const void* q, const int32_t* cu_q,
                                const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t forced_tail,
-                               int32_t* idx_out, hipStream_t st) {
+                               int32_t pool_w, int32_t* idx_out, hipStream_t st) {
   const char *kp = static_cast<const char*>(k), *qp = static_cast<const char*>(q);
   auto launch = [&](auto kernel, size_t lds, int waves) -> hipError_t {
     const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -1060,7 +1134,7 @@ static hipError_t launch_fused(const Shape& s, const void* k, const void* q, con
     if (ea != hipSuccess) return ea;
     const int32_t ranked = s.batch <= 64 && int64_t(s.batch) * s.hkv > compute_units() ? 1 : 0;
     kernel<<<dim3(s.batch * s.hkv), dim3(waves * 64), lds, st>>>(kp, qp, cu_q, cu_kv, cu_k, total_k, forced_tail,
-                                                                      ranked, idx_out, s DLLM_CHECK_PASS);
+                                                                      pool_w, ranked, idx_out, s DLLM_CHECK_PASS);
     return hipGetLastError();
   };
   if (s.group == 4) return launch(select_fused_kernel<ES, D, 4>, FusedLds<ES, D, 4>::bytes, fused_waves<4>());
@@ -1076,9 +1150,9 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
   const int32_t form = g_select_form.load();
   if (form != DLLM_SELECT_FORM_TWO_LAUNCHES && fused_can(s, dt, pool_w, head_sum) &&
       (form == DLLM_SELECT_FORM_ONE_LAUNCH || fused_pays(s)))
-    return dt == DLLM_BF16 ? (s.d == 128 ? launch_fused<2, 128>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, idx_out, st)
-                                         : launch_fused<2, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, idx_out, st))
-                           : launch_fused<4, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, idx_out, st);
+    return dt == DLLM_BF16 ? (s.d == 128 ? launch_fused<2, 128>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, pool_w, idx_out, st)
+                                         : launch_fused<2, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, pool_w, idx_out, st))
+                           : launch_fused<4, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, pool_w, idx_out, st);
   const SelectPlan p = plan_select(s);
   float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_scores);
   hipError_t e;

@@ -158,6 +158,9 @@ def test_select_in_one_launch_edges(dtype, Hq, Hkv, D):
             w.k[off + r:off + r + n] = w.k[off:off + n].clone()
         off += L
     check_select(w, name="edges, rows repeated every 40 positions")
+    # pooling windows reach across tiles (64 positions) and across the runs of tiles of neighbouring waves
+    check_select(w, pool_w=3, name="edges, repeated rows, pooling window 3")
+    check_select(w, pool_w=63, name="edges, repeated rows, pooling window 63")
     check_select_ex(w, 1, 1, False, "edges, forced block of 1 on repeated rows")
     # several rounds of workgroups: 80 sequences are taken in batch order, up to 64 longest list first
     many = custom(42, dtype, 8, 8, D, [700] * 80, [32] * 80, [70] * 80)
