@@ -150,6 +150,13 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch *batch,
 #define DLLM_SELECT_FORM_TWO_LAUNCHES 1
 #define DLLM_SELECT_FORM_ONE_LAUNCH 2 /* wherever the shape allows it; other shapes still take two */
 int32_t dllm_hcsa_set_select_form(int32_t form);
+/*
+ * The form a selection call on this batch takes under the current setting: DLLM_SELECT_FORM_ONE_LAUNCH or
+ * DLLM_SELECT_FORM_TWO_LAUNCHES; -1 if the batch descriptor is invalid (dllm_last_error says why).  Host
+ * only: reads the descriptor, no device memory, launches nothing.  (The compute-unit count is that of the
+ * current device, 256 if none can be queried.)
+ */
+int32_t dllm_hcsa_select_form_of(const dllm_batch *batch, int32_t pool_w, int32_t head_sum);
 
 /*
  * Selection for callers that cannot allocate or hand over device scratch memory: code under HIP graph

@@ -224,6 +224,12 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch* batch, const int32_t* cu_k, in
 
 int32_t dllm_hcsa_set_select_form(int32_t form) { return dllm::set_select_form(form); }
 
+int32_t dllm_hcsa_select_form_of(const dllm_batch* batch, int32_t pool_w, int32_t head_sum) {
+  dllm::Shape s;
+  if (check_batch(batch, &s) != DLLM_OK) return -1;
+  return dllm::select_form_of(s, batch->dtype, pool_w, head_sum);
+}
+
 dllm_status dllm_hcsa_select_static(const dllm_batch* batch, const int32_t* cu_k, int32_t total_k, int32_t max_k,
                                     int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out,
                                     void* hip_stream) {

@@ -34,6 +34,8 @@ hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const voi
                          int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out, void* ws,
                          hipStream_t st);
 
+// the form a selection call of this shape takes under the current setting (ONE_LAUNCH or TWO_LAUNCHES)
+int32_t select_form_of(const Shape& s, dllm_dtype dt, int32_t pool_w, int32_t head_sum);
 int32_t set_select_form(int32_t form);   // DLLM_SELECT_FORM_*; returns the previous one, -1 if form is not one of them
 
 // ---- packing of the kept rows (pack_kernels.hip)

@@ -1142,14 +1142,19 @@ static hipError_t launch_fused(const Shape& s, const void* k, const void* q, con
   return launch(select_fused_kernel<ES, D, 1>, FusedLds<ES, D, 1>::bytes, fused_waves<1>());
 }
 
+int32_t select_form_of(const Shape& s, dllm_dtype dt, int32_t pool_w, int32_t head_sum) {
+  const int32_t form = g_select_form.load();
+  const bool one = form != DLLM_SELECT_FORM_TWO_LAUNCHES && fused_can(s, dt, pool_w, head_sum) &&
+                   (form == DLLM_SELECT_FORM_ONE_LAUNCH || fused_pays(s));
+  return one ? DLLM_SELECT_FORM_ONE_LAUNCH : DLLM_SELECT_FORM_TWO_LAUNCHES;
+}
+
 hipError_t launch_select(const Shape& s, dllm_dtype dt, const void* q, const void* k, const int32_t* cu_q,
                          const int32_t* cu_kv, const int32_t* cu_k, int32_t total_k, int32_t max_k,
                          int32_t pool_w, int32_t forced_tail, int32_t head_sum, int32_t* idx_out, void* ws,
                          hipStream_t st) {
   (void)max_k;
-  const int32_t form = g_select_form.load();
-  if (form != DLLM_SELECT_FORM_TWO_LAUNCHES && fused_can(s, dt, pool_w, head_sum) &&
-      (form == DLLM_SELECT_FORM_ONE_LAUNCH || fused_pays(s)))
+  if (select_form_of(s, dt, pool_w, head_sum) == DLLM_SELECT_FORM_ONE_LAUNCH)
     return dt == DLLM_BF16 ? (s.d == 128 ? launch_fused<2, 128>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, pool_w, idx_out, st)
                                          : launch_fused<2, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, pool_w, idx_out, st))
                            : launch_fused<4, 64>(s, k, q, cu_q, cu_kv, cu_k, total_k, forced_tail, pool_w, idx_out, st);

@@ -28,7 +28,7 @@ DLLM_SELECT_FORM_AUTO, DLLM_SELECT_FORM_TWO_LAUNCHES, DLLM_SELECT_FORM_ONE_LAUNC
 
 EXPORTS = [
     "dllm_hcsa_select_workspace", "dllm_hcsa_select", "dllm_hcsa_select_ex", "dllm_hcsa_select_static",
-    "dllm_hcsa_set_select_form",
+    "dllm_hcsa_set_select_form", "dllm_hcsa_select_form_of",
     "dllm_hcsa_attend_workspace", "dllm_hcsa_attend",
     "dllm_dense_refresh_attend_workspace", "dllm_dense_refresh_attend",
     "dllm_hcsa_pack", "dllm_hcsa_precondition_errors",
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.dllm_hcsa_select_ex.argtypes = [P, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.dllm_hcsa_set_select_form.restype = i32
         L.dllm_hcsa_set_select_form.argtypes = [i32]
+        L.dllm_hcsa_select_form_of.restype = i32
+        L.dllm_hcsa_select_form_of.argtypes = [P, i32, i32]
         L.dllm_hcsa_select_static.restype = ctypes.c_int
         L.dllm_hcsa_select_static.argtypes = [P, vp, i32, i32, i32, i32, i32, vp, vp]
         L.dllm_hcsa_attend_workspace.restype = sz
@@ -202,6 +204,14 @@ def dllm_hcsa_select_ex(batch: DllmBatch, cu_k: torch.Tensor, total_k: int, max_
 
 
 DLLM_SELECT_STATIC_BYTES = 32 << 20
+
+
+def dllm_hcsa_select_form_of(batch: DllmBatch, pool_w: int = 1, head_sum: bool = False) -> int:
+    """Which of its two forms a selection call on this batch takes under the current setting (DLLM_SELECT_FORM_*)."""
+    form = int(lib().dllm_hcsa_select_form_of(ctypes.byref(batch), int(pool_w), int(bool(head_sum))))
+    if form < 0:
+        raise ValueError(last_error())
+    return form
 
 
 def dllm_hcsa_set_select_form(form: int) -> int:

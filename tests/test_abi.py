@@ -57,6 +57,53 @@ def good_batch():
 FAKE = ctypes.c_void_p(0x30000)
 
 
+def shaped_batch(batch, hq, hkv, d, total_kv, max_kv, dtype=None):
+    b = good_batch()
+    b.dtype = hcsa.DLLM_BF16 if dtype is None else dtype
+    b.batch, b.n_q_heads, b.n_kv_heads, b.head_dim = batch, hq, hkv, d
+    b.q_stride_tok, b.q_stride_head = hq * d, d
+    b.kv_stride_tok, b.kv_stride_head = hkv * d, d
+    b.total_q, b.max_q = 32 * batch, 32
+    b.total_kv, b.max_kv = total_kv, max_kv
+    return b
+
+
+def test_which_form_selection_takes_follows_the_documented_rule():
+    """Host logic only (no GPU: 256 compute units are assumed).  One launch needs per-head selection, at most four
+    query heads per KV head, rows of at most 256 bytes, lists of at most 8192, (sequence, KV head) pairs that fill
+    the compute units in whole rounds or nearly, and a fairly even batch; the setter overrides the size rule only."""
+    ONE, TWO = hcsa.DLLM_SELECT_FORM_ONE_LAUNCH, hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES
+    form = lambda b, pool_w=1, head_sum=False: hcsa.dllm_hcsa_select_form_of(b, pool_w, head_sum)
+    assert hcsa.lib().dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_AUTO) >= 0
+    try:
+        c5 = shaped_batch(32, 32, 8, 128, 24 * 8192 + 8 * 2048, 8192)        # the mixed grouped-query burst: 256 pairs
+        assert form(c5) == ONE and form(c5, pool_w=3) == ONE and form(c5, head_sum=True) == TWO
+        c3 = shaped_batch(16, 32, 32, 128, 34482, 3411)                       # ragged: mean length 63 % of the longest
+        assert form(c3) == TWO
+        assert form(shaped_batch(16, 32, 32, 128, 16 * 3411, 3411)) == ONE    # the same, even: two full rounds
+        assert form(shaped_batch(4, 32, 8, 128, 4 * 8192, 8192)) == TWO       # 32 pairs: most compute units idle
+        assert form(shaped_batch(23, 32, 8, 128, 23 * 8192, 8192)) == TWO     # 184 pairs: under 3/4 of a round
+        assert form(shaped_batch(24, 32, 8, 128, 24 * 8192, 8192)) == ONE     # 192 pairs
+        assert form(shaped_batch(48, 32, 8, 128, 48 * 4096, 4096)) == TWO     # 384 pairs: the second round half empty
+        assert form(shaped_batch(52, 32, 8, 128, 52 * 4096, 4096)) == ONE     # 416 pairs: 81 % of two rounds
+        assert form(shaped_batch(32, 32, 8, 128, 32 * 8193, 8193)) == TWO     # a list too long for the registers
+        assert form(shaped_batch(32, 64, 8, 128, 32 * 8192, 8192)) == TWO     # eight query heads per KV head
+        assert form(shaped_batch(32, 32, 8, 128, 32 * 8192, 8192, hcsa.DLLM_F32)) == TWO   # 512-byte rows
+        assert form(shaped_batch(32, 32, 8, 64, 32 * 8192, 8192, hcsa.DLLM_F32)) == ONE
+        hcsa.dllm_hcsa_set_select_form(TWO)
+        assert form(c5) == TWO
+        hcsa.dllm_hcsa_set_select_form(ONE)
+        assert form(c3) == ONE and form(shaped_batch(4, 32, 8, 128, 4 * 8192, 8192)) == ONE
+        assert form(c5, head_sum=True) == TWO and form(shaped_batch(32, 64, 8, 128, 32 * 8192, 8192)) == TWO
+        bad = shaped_batch(4, 32, 8, 128, 100, 50)
+        bad.head_dim = 96
+        assert hcsa.lib().dllm_hcsa_select_form_of(ctypes.byref(bad), 1, 0) == -1 and "head_dim" in hcsa.last_error()
+    finally:
+        hcsa.dllm_hcsa_set_select_form(hcsa.DLLM_SELECT_FORM_AUTO)
+
+
+
+
 def select_status(b, cu_k=FAKE, total_k=100, max_k=50, pool_w=1, idx=FAKE, ws=FAKE, ws_bytes=1 << 40):
     return hcsa.lib().dllm_hcsa_select(ctypes.byref(b), cu_k, total_k, max_k, pool_w, idx, ws, ws_bytes, None)
 

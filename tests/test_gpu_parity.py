@@ -91,6 +91,16 @@ def test_select_config3_full():
     check_select(synth.config(3))
 
 
+def test_benchmark_workloads_take_the_selection_form_the_documentation_says():
+    """On the 256 compute units of an MI355X the mixed grouped-query burst is selected in one launch (also with
+    the pooling window), the ragged batch in two; the parity cases above run both forms on both either way."""
+    d5, d3 = workload.DeviceWorkload(synth.config(5)), workload.DeviceWorkload(synth.config(3))
+    assert hcsa.dllm_hcsa_select_form_of(d5.batch) == hcsa.DLLM_SELECT_FORM_ONE_LAUNCH
+    assert hcsa.dllm_hcsa_select_form_of(d5.batch, pool_w=3) == hcsa.DLLM_SELECT_FORM_ONE_LAUNCH
+    assert hcsa.dllm_hcsa_select_form_of(d5.batch, head_sum=True) == hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES
+    assert hcsa.dllm_hcsa_select_form_of(d3.batch) == hcsa.DLLM_SELECT_FORM_TWO_LAUNCHES
+
+
 def test_select_config5_gqa_full():
     check_select(synth.config(5))
 
