@@ -142,7 +142,7 @@ dllm_status dllm_hcsa_select_ex(const dllm_batch *batch,
  * library takes the one-launch form when the shape allows it, the (sequence, KV head) pairs fill the
  * compute units in whole rounds or nearly (at least 3/4 of them in a single round, 4/5 of the last of
  * several) and the batch is fairly even (total_kv >= 3/4 * batch * max_kv), where it measures 5 to
- * 30 % faster.  This call overrides that choice for the whole process (all threads, all later calls);
+ * 30 % faster, and for calls so small (total_kv * n_kv_heads <= 4096) that only launch latency counts.  This call overrides that choice for the whole process (all threads, all later calls);
  * it exists for measurement and for tests that must reach both forms.  Returns the previous setting,
  * or -1 (and changes nothing) for a value that is none of the three.
  */

@@ -82,6 +82,8 @@ def test_which_form_selection_takes_follows_the_documented_rule():
         assert form(c3) == TWO
         assert form(shaped_batch(16, 32, 32, 128, 16 * 3411, 3411)) == ONE    # the same, even: two full rounds
         assert form(shaped_batch(4, 32, 8, 128, 4 * 8192, 8192)) == TWO       # 32 pairs: most compute units idle
+        assert form(shaped_batch(1, 4, 4, 64, 256, 256, hcsa.DLLM_F32)) == ONE   # tiny: launch latency only
+        assert form(shaped_batch(1, 32, 32, 128, 1024, 1024)) == TWO          # one layer-sized sequence
         assert form(shaped_batch(23, 32, 8, 128, 23 * 8192, 8192)) == TWO     # 184 pairs: under 3/4 of a round
         assert form(shaped_batch(24, 32, 8, 128, 24 * 8192, 8192)) == ONE     # 192 pairs
         assert form(shaped_batch(48, 32, 8, 128, 48 * 4096, 4096)) == TWO     # 384 pairs: the second round half empty
